@@ -1,0 +1,150 @@
+"""ctypes front end of the CPU oracle (``ne_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke()`` and by the
+``cpu_baseline`` leg of ``bench.py``.  Nothing under the product package imports it, and it imports
+nothing from the product package.  All arrays are host numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ne_oracle.c")
+_SO = os.path.join(_HERE, "libne_oracle.so")
+
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with gcc.  No fast-math, no FMA contraction: plain IEEE fp64."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fast-math",
+               "-Wall", "-Wextra", "-o", _SO, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _SO
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build(force=False)
+    lib = ctypes.CDLL(_SO)
+    c = ctypes
+    p = c.c_void_p
+    lib.oracle_philox4x32_10.argtypes = [p, p, p]
+    lib.oracle_philox4x32_10.restype = None
+    lib.oracle_init_tables.argtypes = [c.c_int64, c.c_int32, c.c_uint64, p, p]
+    lib.oracle_init_tables.restype = None
+    lib.oracle_build_alias.argtypes = [p, c.c_int64, p, p, p]
+    lib.oracle_build_alias.restype = c.c_int
+    lib.oracle_sample_negatives.argtypes = [c.c_uint64, c.c_uint64, c.c_int64, c.c_int32, p, p,
+                                            c.c_int64, c.c_int32, p]
+    lib.oracle_sample_negatives.restype = None
+    lib.oracle_sample_shared_negatives.argtypes = [c.c_uint64, c.c_uint64, c.c_int32, p, p,
+                                                   c.c_int64, c.c_int32, p]
+    lib.oracle_sample_shared_negatives.restype = None
+    lib.oracle_train_batch.argtypes = [p, p, c.c_int64, c.c_int32, p, c.c_int64, c.c_int32,
+                                       c.c_float, p]
+    lib.oracle_train_batch.restype = c.c_int
+    lib.oracle_eval_loss.argtypes = [p, p, c.c_int64, c.c_int32, p, c.c_int64, c.c_int32, p]
+    lib.oracle_eval_loss.restype = c.c_double
+    _lib = lib
+    return lib
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _chk(a, dtype, name):
+    if not isinstance(a, np.ndarray) or a.dtype != dtype or not a.flags["C_CONTIGUOUS"]:
+        raise TypeError(f"{name}: need a C-contiguous numpy array of {np.dtype(dtype)}")
+    return a
+
+
+def philox4x32_10(ctr, key) -> np.ndarray:
+    """Four 32-bit outputs of Philox4x32-10 for counter (c0..c3) and key (k0, k1)."""
+    ctr = np.ascontiguousarray(ctr, dtype=np.uint32)
+    key = np.ascontiguousarray(key, dtype=np.uint32)
+    assert ctr.shape == (4,) and key.shape == (2,)
+    out = np.empty(4, dtype=np.uint32)
+    _load().oracle_philox4x32_10(_ptr(ctr), _ptr(key), _ptr(out))
+    return out
+
+
+def init_tables(num_nodes: int, dim: int, seed: int):
+    """(vertex, context) fp32 tables: vertex ~ U(-0.5/dim, 0.5/dim), context = 0."""
+    X = np.empty((num_nodes, dim), dtype=np.float32)
+    C = np.empty((num_nodes, dim), dtype=np.float32)
+    _load().oracle_init_tables(num_nodes, dim, seed, _ptr(X), _ptr(C))
+    return X, C
+
+
+def build_alias(degree: np.ndarray):
+    """Alias table for P(i) ~ degree_i^0.75.  Returns (thr_q uint32[n], alias uint32[n], prob f64[n])."""
+    degree = _chk(np.ascontiguousarray(degree, dtype=np.uint32), np.uint32, "degree")
+    n = degree.shape[0]
+    thr = np.empty(n, dtype=np.uint32)
+    alias = np.empty(n, dtype=np.uint32)
+    prob = np.empty(n, dtype=np.float64)
+    rc = _load().oracle_build_alias(_ptr(degree), n, _ptr(thr), _ptr(alias), _ptr(prob))
+    if rc != 0:
+        raise ValueError(f"oracle_build_alias failed ({rc}): empty input or all degrees zero")
+    return thr, alias, prob
+
+
+def sample_negatives(seed: int, sample_base: int, B: int, K: int, thr: np.ndarray,
+                     alias: np.ndarray, base: int = 0) -> np.ndarray:
+    """int32[B][K] negative ids for samples sample_base .. sample_base+B-1."""
+    _chk(thr, np.uint32, "thr")
+    _chk(alias, np.uint32, "alias")
+    out = np.empty((B, K), dtype=np.int32)
+    _load().oracle_sample_negatives(seed, sample_base, B, K, _ptr(thr), _ptr(alias), thr.shape[0],
+                                    base, _ptr(out))
+    return out
+
+
+def sample_shared_negatives(seed: int, batch_index: int, N: int, thr: np.ndarray, alias: np.ndarray,
+                            base: int = 0) -> np.ndarray:
+    """int32[N] negative ids shared by every pair of batch `batch_index`."""
+    _chk(thr, np.uint32, "thr")
+    _chk(alias, np.uint32, "alias")
+    out = np.empty(N, dtype=np.int32)
+    _load().oracle_sample_shared_negatives(seed, batch_index, N, _ptr(thr), _ptr(alias),
+                                           thr.shape[0], base, _ptr(out))
+    return out
+
+
+def train_batch(X: np.ndarray, C: np.ndarray, pairs: np.ndarray, neg: np.ndarray, lr: float) -> None:
+    """One minibatch-synchronous SGNS step, in place on X and C (fp32 [V][d])."""
+    _chk(X, np.float32, "X")
+    _chk(C, np.float32, "C")
+    _chk(pairs, np.int32, "pairs")
+    _chk(neg, np.int32, "neg")
+    V, d = X.shape
+    B = pairs.shape[0]
+    assert C.shape == X.shape and pairs.shape == (B, 2)
+    K = neg.shape[1] if B > 0 else (neg.shape[1] if neg.ndim == 2 else 0)
+    assert neg.shape == (B, K)
+    rc = _load().oracle_train_batch(_ptr(X), _ptr(C), V, d, _ptr(pairs), B, K, np.float32(lr),
+                                    _ptr(neg))
+    if rc != 0:
+        raise ValueError(f"oracle_train_batch failed ({rc})")
+
+
+def eval_loss(X: np.ndarray, C: np.ndarray, pairs: np.ndarray, neg: np.ndarray) -> float:
+    """Sum over the batch of -log s(s_0) - sum_k log s(-s_k) at the current tables."""
+    _chk(X, np.float32, "X")
+    _chk(C, np.float32, "C")
+    _chk(pairs, np.int32, "pairs")
+    _chk(neg, np.int32, "neg")
+    V, d = X.shape
+    B = pairs.shape[0]
+    K = neg.shape[1]
+    assert neg.shape == (B, K)
+    return float(_load().oracle_eval_loss(_ptr(X), _ptr(C), V, d, _ptr(pairs), B, K, _ptr(neg)))
