@@ -1,0 +1,130 @@
+/*
+ * ne.h - C ABI of the MI355X (gfx950) SGNS node-embedding training library.
+ *
+ * The library runs the embedding-training loop of the paper's Algorithm 1 (Sec. II-A "Training
+ * Process") on one GPU: for a batch of positive (src, ctx) edge samples it draws K negative context
+ * nodes per sample, scores vertex[src] against context[ctx] (label 1) and context[neg_k] (label 0)
+ * with a dot product and a sigmoid, and applies the SGD update to both embedding tables.  Data
+ * formats follow Table I: node ids are 4 bytes, a sample is an 8-byte (src, ctx) pair, and both
+ * embedding tables are row-major fp32 [num_nodes][dim].
+ *
+ * Update semantics are minibatch-synchronous: every gradient of a batch is evaluated at the tables
+ * as they were before the batch, contributions to the same row are summed, and the sums are applied
+ * once (the paper trains "in fully synchronous style", Sec. III-B).
+ *
+ * Conventions
+ *  - "_dev" pointers are device memory owned by the caller; "_host" pointers are host memory.  The
+ *    library never allocates or frees device memory.  The opaque handles are small host structs.
+ *  - hip_stream is a hipStream_t passed as void* (NULL = the default stream).  Unless stated
+ *    otherwise a call enqueues its work on that stream and returns without synchronising.
+ *  - Every call returns NE_OK or a negative ne_status.  Argument errors are detected on the host
+ *    before anything is enqueued.  ne_last_error() describes the last failure on this thread.
+ *  - Node ids inside pairs_dev are not range-checked on the training path; ne_validate_pairs does it.
+ *  - Random draws are Philox4x32-10 (Salmon et al., SC'11) keyed by the tables' seed and addressed
+ *    by (sample index, k), so results do not depend on how samples are split into calls.
+ */
+#ifndef NE_H
+#define NE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ne_tables ne_tables; /* host handle: pointers + shape of the two embedding tables   */
+typedef struct ne_alias ne_alias;   /* host handle: a device alias table over ids [base, base+n)   */
+
+typedef enum {
+    NE_OK = 0,
+    NE_ERR_ARG = -1,   /* bad argument (null pointer, shape, range, too-small buffer)              */
+    NE_ERR_STATE = -2, /* handles that do not belong together                                      */
+    NE_ERR_HIP = -3,   /* a HIP runtime call or kernel launch failed                               */
+    NE_ERR_NOMEM = -4  /* host allocation failed                                                   */
+} ne_status;
+
+enum { NE_MAX_DIM = 1024, NE_MAX_NEGATIVES = 63 };
+
+/*
+ * Bind the vertex and context embedding matrices of Sec. II-A ("Embedding Representation") and,
+ * if init != 0, initialise them on the stream: vertex ~ U(-0.5/dim, 0.5/dim), context = 0.
+ * Element (row, col) of vertex is ((r >> 9) + 0.5) * 2^-23 - 0.5, divided by dim, where r is output
+ * word col%4 of Philox(key = seed, counter = (row, 0, col/4, 1)).
+ *   vertex_dev, context_dev : device, fp32 [num_nodes][dim] row-major, 16-byte aligned, caller-owned,
+ *                             must stay valid while the handle is used.
+ *   0 < num_nodes < 2^31;  dim % 4 == 0, 4 <= dim <= NE_MAX_DIM.
+ *   seed keys every random draw made through this handle.
+ * *out receives a handle to free with ne_destroy_tables.  Errors: NE_ERR_ARG, NE_ERR_NOMEM, NE_ERR_HIP.
+ */
+ne_status ne_create_tables(ne_tables** out, int64_t num_nodes, int32_t dim, float* vertex_dev,
+                           float* context_dev, uint64_t seed, int32_t init, void* hip_stream);
+
+/*
+ * Build the negative-sampling table (Algorithm 1, NegativeSample) for the id range [base, base+n):
+ * P(base+i) proportional to degree_host[i]^0.75, as a Walker/Vose alias table of n entries
+ * {uint32 threshold, uint32 alias} (8 bytes each) written to alias_dev.
+ *   degree_host : host, uint32[n], read during the call only.  At least one entry must be non-zero.
+ *   alias_dev   : device, 8*n bytes, 8-byte aligned, caller-owned, must outlive the handle's use.
+ *   0 < n, 0 <= base, base + n < 2^31.
+ * The table is built on the host (fp64, sequential, deterministic) and copied on the stream; the
+ * call returns after the copy has completed.  A draw uses the four Philox words r0..r3:
+ * slot = floor(((r0<<32)|r1) * n / 2^64); id = base + (r2 < threshold[slot] ? slot : alias[slot]).
+ * Errors: NE_ERR_ARG (also when all degrees are zero), NE_ERR_NOMEM, NE_ERR_HIP.
+ */
+ne_status ne_build_neg_alias(ne_alias** out, const uint32_t* degree_host, int64_t n, int32_t base,
+                             void* alias_dev, void* hip_stream);
+
+/* Bytes of device scratch ne_train_batch needs for a batch of B pairs (0 if an argument is invalid). */
+size_t ne_staging_bytes(int64_t B, int32_t dim, int32_t K);
+
+/*
+ * One minibatch-synchronous SGNS step (Algorithm 1, one iteration of the embedding-training loop
+ * for every pair of the batch).
+ *   pairs_dev   : device, int32[B][2] = (src, ctx), 8-byte aligned; ids must lie in [0, num_nodes).
+ *   K           : negatives per pair, 0 <= K <= NE_MAX_NEGATIVES.  Negative k of pair b is the alias
+ *                 draw for Philox(key = seed, counter = (idx_lo, idx_hi, k, 0)), idx = sample_base + b.
+ *                 The alias range must lie inside [0, num_nodes).
+ *   lr          : learning rate of this batch (the caller owns the schedule).
+ *   staging_dev : device scratch of at least ne_staging_bytes(B, dim, K) bytes, 16-byte aligned;
+ *                 contents are overwritten.  staging_bytes is its size.
+ *   neg_out_dev : NULL, or device int32[B][K] that receives the negative ids used.
+ * With x = vertex[src], c_0 = context[ctx], c_k = context[neg_k] read before the batch:
+ *   s_j = <x, c_j>,  g_0 = 1 - sigmoid(s_0),  g_k = -sigmoid(s_k),
+ *   vertex[src] += lr * sum_j g_j c_j,   context[id_j] += lr * g_j x   (fp32 atomic adds).
+ * B == 0 is a no-op.  Calls on one pair of tables must be ordered by the stream.
+ * Errors: NE_ERR_ARG, NE_ERR_STATE, NE_ERR_HIP.
+ */
+ne_status ne_train_batch(ne_tables* tables, const ne_alias* alias, const int32_t* pairs_dev, int64_t B,
+                         int32_t K, float lr, uint64_t sample_base, void* staging_dev,
+                         size_t staging_bytes, int32_t* neg_out_dev, void* hip_stream);
+
+/*
+ * Loss of a batch at the current tables with the same negatives ne_train_batch would draw; nothing
+ * is updated.  Adds  sum_b [ -log sigmoid(s_b0) - sum_k log sigmoid(-s_bk) ]  (fp32 terms, fp64 sum)
+ * to *loss_sum_dev.
+ *   loss_sum_dev : device double, caller-zeroed, read back by the caller after syncing the stream.
+ *   neg_out_dev  : NULL, or device int32[B][K] that receives the negative ids.
+ * Errors: NE_ERR_ARG, NE_ERR_STATE, NE_ERR_HIP.
+ */
+ne_status ne_eval_loss(const ne_tables* tables, const ne_alias* alias, const int32_t* pairs_dev,
+                       int64_t B, int32_t K, uint64_t sample_base, double* loss_sum_dev,
+                       int32_t* neg_out_dev, void* hip_stream);
+
+/*
+ * Debug helper for the sample format of Table I: counts ids in pairs_dev int32[B][2] that fall
+ * outside [0, num_nodes) and adds the count to *bad_count_dev (device uint64, caller-zeroed).
+ */
+ne_status ne_validate_pairs(const ne_tables* tables, const int32_t* pairs_dev, int64_t B,
+                            unsigned long long* bad_count_dev, void* hip_stream);
+
+void ne_destroy_tables(ne_tables* tables);
+void ne_destroy_alias(ne_alias* alias);
+
+/* Message for the last non-NE_OK status returned on the calling thread (valid until the next call). */
+const char* ne_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NE_H */

@@ -1,0 +1,193 @@
+"""Python binding of libne.so, the MI355X SGNS node-embedding training library.
+
+Argument marshalling only: every function below forwards to the C entry point of the same name
+(see include/ne.h).  torch is used for device memory and streams; all arithmetic runs in the HIP
+kernels.  Importing the package does not load the library; the first call does, and it raises if
+the library has not been built (there is no fallback path).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libne.so")
+
+NE_OK = 0
+NE_ERR_ARG = -1
+NE_ERR_STATE = -2
+NE_ERR_HIP = -3
+NE_ERR_NOMEM = -4
+NE_MAX_DIM = 1024
+NE_MAX_NEGATIVES = 63
+
+EXPORTS = (
+    "ne_create_tables", "ne_build_neg_alias", "ne_staging_bytes", "ne_train_batch", "ne_eval_loss",
+    "ne_validate_pairs", "ne_destroy_tables", "ne_destroy_alias", "ne_last_error",
+)
+
+_lib = None
+
+
+class NeError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"ne status {status}: {message}")
+        self.status = status
+
+
+def lib() -> ctypes.CDLL:
+    """Load libne.so (once).  Raises if it is missing: build it with paper_2005_13789_amd/build.py."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} not found: run `python -m paper_2005_13789_amd.build` (hipcc, gfx950) first")
+    L = ctypes.CDLL(LIB_PATH)
+    c = ctypes
+    vp = c.c_void_p
+    L.ne_create_tables.argtypes = [c.POINTER(vp), c.c_int64, c.c_int32, vp, vp, c.c_uint64, c.c_int32, vp]
+    L.ne_create_tables.restype = c.c_int
+    L.ne_build_neg_alias.argtypes = [c.POINTER(vp), vp, c.c_int64, c.c_int32, vp, vp]
+    L.ne_build_neg_alias.restype = c.c_int
+    L.ne_staging_bytes.argtypes = [c.c_int64, c.c_int32, c.c_int32]
+    L.ne_staging_bytes.restype = c.c_size_t
+    L.ne_train_batch.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_float, c.c_uint64, vp, c.c_size_t, vp, vp]
+    L.ne_train_batch.restype = c.c_int
+    L.ne_eval_loss.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_uint64, vp, vp, vp]
+    L.ne_eval_loss.restype = c.c_int
+    L.ne_validate_pairs.argtypes = [vp, vp, c.c_int64, vp, vp]
+    L.ne_validate_pairs.restype = c.c_int
+    L.ne_destroy_tables.argtypes = [vp]
+    L.ne_destroy_tables.restype = None
+    L.ne_destroy_alias.argtypes = [vp]
+    L.ne_destroy_alias.restype = None
+    L.ne_last_error.argtypes = []
+    L.ne_last_error.restype = c.c_char_p
+    _lib = L
+    return L
+
+
+def _check(status: int) -> None:
+    if status != NE_OK:
+        raise NeError(status, lib().ne_last_error().decode("utf-8", "replace"))
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def _dev_ptr(t, dtype, name: str) -> int:
+    if t is None:
+        return 0
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{name}: need a contiguous CUDA tensor of {dtype}")
+    return t.data_ptr()
+
+
+class Tables:
+    """Handle from ne_create_tables; keeps the two table tensors alive."""
+
+    def __init__(self, handle: int, vertex: torch.Tensor, context: torch.Tensor, seed: int):
+        self.handle = handle
+        self.vertex = vertex
+        self.context = context
+        self.seed = seed
+        self.num_nodes, self.dim = vertex.shape
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.ne_destroy_tables(self.handle)
+            self.handle = None
+
+
+class Alias:
+    """Handle from ne_build_neg_alias; keeps the device table tensor alive."""
+
+    def __init__(self, handle: int, table: torch.Tensor, n: int, base: int):
+        self.handle = handle
+        self.table = table
+        self.n = n
+        self.base = base
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.ne_destroy_alias(self.handle)
+            self.handle = None
+
+
+def ne_create_tables(vertex: torch.Tensor, context: torch.Tensor, seed: int, init: bool = True,
+                     stream=None) -> Tables:
+    """Bind fp32 [num_nodes][dim] CUDA tensors; if init, vertex ~ U(-0.5/dim, 0.5/dim), context = 0."""
+    vp = _dev_ptr(vertex, torch.float32, "vertex")
+    cp = _dev_ptr(context, torch.float32, "context")
+    if vertex.dim() != 2 or vertex.shape != context.shape:
+        raise TypeError("vertex and context must both be [num_nodes][dim]")
+    out = ctypes.c_void_p()
+    _check(lib().ne_create_tables(ctypes.byref(out), vertex.shape[0], vertex.shape[1], vp, cp,
+                                  seed & (2**64 - 1), 1 if init else 0, _stream_ptr(stream)))
+    return Tables(out.value, vertex, context, seed)
+
+
+def ne_build_neg_alias(degree_host, base: int, alias_table: torch.Tensor, stream=None) -> Alias:
+    """degree_host: CPU uint32-valued array/tensor [n]; alias_table: CUDA int32 [n][2] to be filled."""
+    import numpy as np
+    if isinstance(degree_host, torch.Tensor):
+        degree_host = degree_host.cpu().numpy()
+    deg = np.ascontiguousarray(degree_host, dtype=np.uint32)
+    n = int(deg.shape[0])
+    ap = _dev_ptr(alias_table, torch.int32, "alias_table")
+    if alias_table.numel() < 2 * n:
+        raise TypeError("alias_table needs 2*n int32 elements")
+    out = ctypes.c_void_p()
+    _check(lib().ne_build_neg_alias(ctypes.byref(out), deg.ctypes.data, n, base, ap, _stream_ptr(stream)))
+    return Alias(out.value, alias_table, n, base)
+
+
+def ne_staging_bytes(B: int, dim: int, K: int) -> int:
+    return int(lib().ne_staging_bytes(B, dim, K))
+
+
+def ne_train_batch(tables: Tables, alias: Alias | None, pairs: torch.Tensor, K: int, lr: float,
+                   sample_base: int, staging: torch.Tensor, neg_out: torch.Tensor | None = None,
+                   stream=None, B: int | None = None) -> None:
+    """One minibatch-synchronous SGNS step on pairs int32 [B][2] (CUDA)."""
+    if B is None:
+        B = int(pairs.shape[0])
+    pp = _dev_ptr(pairs, torch.int32, "pairs")
+    sp = _dev_ptr(staging, torch.uint8, "staging")
+    np_ = _dev_ptr(neg_out, torch.int32, "neg_out")
+    if neg_out is not None and neg_out.numel() < B * K:
+        raise TypeError("neg_out needs B*K int32 elements")
+    _check(lib().ne_train_batch(tables.handle, alias.handle if alias else None, pp, B, K, lr, sample_base,
+                                sp, staging.numel(), np_, _stream_ptr(stream)))
+
+
+def ne_eval_loss(tables: Tables, alias: Alias | None, pairs: torch.Tensor, K: int, sample_base: int,
+                 loss_sum: torch.Tensor, neg_out: torch.Tensor | None = None, stream=None,
+                 B: int | None = None) -> None:
+    """Adds the batch's summed SGNS loss to loss_sum (CUDA float64 scalar tensor)."""
+    if B is None:
+        B = int(pairs.shape[0])
+    pp = _dev_ptr(pairs, torch.int32, "pairs")
+    lp = _dev_ptr(loss_sum, torch.float64, "loss_sum")
+    np_ = _dev_ptr(neg_out, torch.int32, "neg_out")
+    if neg_out is not None and neg_out.numel() < B * K:
+        raise TypeError("neg_out needs B*K int32 elements")
+    _check(lib().ne_eval_loss(tables.handle, alias.handle if alias else None, pp, B, K, sample_base, lp, np_,
+                              _stream_ptr(stream)))
+
+
+def ne_validate_pairs(tables: Tables, pairs: torch.Tensor, bad_count: torch.Tensor, stream=None) -> None:
+    """Adds the number of out-of-range ids in pairs to bad_count (CUDA int64 scalar tensor)."""
+    pp = _dev_ptr(pairs, torch.int32, "pairs")
+    bp = _dev_ptr(bad_count, torch.int64, "bad_count")
+    _check(lib().ne_validate_pairs(tables.handle, pp, int(pairs.shape[0]), bp, _stream_ptr(stream)))
+
+
+def ne_last_error() -> str:
+    return lib().ne_last_error().decode("utf-8", "replace")
