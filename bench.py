@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Throughput of the SGNS training hot path on one MI355X.
+
+A step is one ne_train_batch call (negative sampling, row gather, scoring, gradient formation and
+the scatter update) on one batch of synthetic positive pairs that already reside in HBM.
+
+Workloads (synthetic R-MAT stand-ins for the paper's graphs):
+  c3  one GPU's partition at paper scale: 100 M nodes, dim 128, both tables resident (102 GB), pairs
+      pre-bucketed over a 4x4 (src-block, ctx-block) grid, K=5 negatives from the ctx block.  Default:
+      it is the configuration the HBM-bandwidth target is stated on.
+  c2  1 M nodes / 20 M edges, walks of 80, window 5, dim 128, K=5, batch 65536.
+  c4  20 M nodes, dim 512, K=10, batch 32768.
+  c1  10 k nodes, dim 128, K=5, batch 4096 (the parity configuration; cache resident).
+
+Prints one JSON line.  --gpus above 1 is refused: this build is single-GPU.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import paper_2005_13789_amd as ne  # noqa: E402
+import workloads as wl  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per train-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see
+# profiles/), scaled by the factor a plain copy kernel of known size reads on the same counters.
+# None = not measured for that workload.
+TRAFFIC_BYTES_PER_LAUNCH = {"c1": None, "c2": None, "c3": None, "c4": None}
+
+WORKLOADS = {
+    "c1": dict(V=10_000, edges=100_000, d=128, K=5, B=4096, grid=1, abc=(0.57, 0.19, 0.19), walk=(40, 5), seed=0),
+    "c2": dict(V=1_000_000, edges=20_000_000, d=128, K=5, B=65536, grid=1, abc=(0.57, 0.19, 0.19), walk=(80, 5), seed=1),
+    "c3": dict(V=100_000_000, edges=2_000_000_000, d=128, K=5, B=65536, grid=4, abc=(0.57, 0.19, 0.19), walk=None, seed=2),
+    "c4": dict(V=20_000_000, edges=400_000_000, d=512, K=10, B=32768, grid=1, abc=(0.57, 0.19, 0.19), walk=None, seed=3),
+}
+
+
+def algorithmic_bytes_per_pair(d: int, K: int) -> int:
+    """Every touched row read once and written once, plus the pair and one alias entry per negative."""
+    return 2 * (2 + K) * 4 * d + 8 + 8 * K
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def build_workload(name: str, n_batches: int, dev):
+    w = WORKLOADS[name]
+    V, d, K, B, grid, seed = w["V"], w["d"], w["K"], w["B"], w["grid"], w["seed"]
+    t0 = time.time()
+    if w["walk"] is not None:
+        # real graph + random walks (host for the small case, device for 1 M nodes)
+        gdev = "cpu" if V <= 100_000 else dev
+        g = wl.build_graph(V, wl.rmat_edges(V, w["edges"], seed, w["abc"], device=gdev))
+        L, win = w["walk"]
+        pairs = wl.walk_pairs(g, L, win, n_batches * B, seed).to(dev)
+        degree = g.degree
+        del g
+    else:
+        degree = wl.rmat_degrees(V, w["edges"], seed, w["abc"], device=dev)
+        # extra pairs so that every bucket can be cut to whole batches
+        pairs = wl.rmat_pairs(V, n_batches * B + grid * grid * B, seed, w["abc"], device=dev)
+    log(f"{name}: graph/pairs generated in {time.time() - t0:.1f}s")
+    bp = wl.bucket_pairs(pairs, V, grid)
+    sched = [s for s in wl.orthogonal_schedule(bp, B) if s[1] == B]
+    if len(sched) < n_batches:
+        # cycle through the schedule again (walk pairs may be reused across epochs, Sec. V-C)
+        sched = (sched * (n_batches // max(len(sched), 1) + 1))
+    sched = sched[:n_batches]
+    return w, degree, bp, sched
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", default="c3", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-batches", type=int, default=0, help="oracle batches to time (0 = auto)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    name = args.workload
+    n_batches = args.steps + args.warmup
+    w, degree, bp, sched = build_workload(name, n_batches, dev)
+    V, d, K, B, grid, seed = w["V"], w["d"], w["K"], w["B"], w["grid"], w["seed"]
+
+    t0 = time.time()
+    vertex = torch.empty((V, d), dtype=torch.float32, device=dev)
+    context = torch.empty((V, d), dtype=torch.float32, device=dev)
+    workspace = torch.empty(ne.ne_workspace_bytes(d, B, K), dtype=torch.uint8, device=dev)
+    tables = ne.ne_create_tables(vertex, context, seed, init=True, max_batch=B, max_negatives=K, workspace=workspace)
+    # one alias table per context block (a GPU's context partition is fixed; negatives come from it)
+    block = bp.block_rows
+    deg_host = degree.to(torch.int64).clamp_(max=2**32 - 1).cpu().numpy().astype(np.uint32)
+    aliases = []
+    for j in range(grid):
+        lo, hi = j * block, min((j + 1) * block, V)
+        table = torch.empty((hi - lo, 2), dtype=torch.int32, device=dev)
+        aliases.append(ne.ne_build_neg_alias(deg_host[lo:hi], lo, table))
+    torch.cuda.synchronize()
+    log(f"tables + {grid} alias table(s) ready in {time.time() - t0:.1f}s; "
+        f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated")
+
+    total_pairs = n_batches * B
+    lrs = [np.float32(wl.linear_decay_lr(0.025, i * B, total_pairs)) for i in range(n_batches)]
+    pairs = bp.pairs
+
+    def step(i):
+        s, n, _, j = sched[i]
+        ne.ne_train_batch(tables, aliases[j], pairs[s:s + n], K, float(lrs[i]), i * B)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ne.ne_profile_enable(tables, 4, args.steps // 4 + 2)
+    t_start = time.perf_counter()
+    for i in range(args.warmup, n_batches):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    kern_ms, kern_n = ne.ne_profile_read(tables)
+    ne.ne_profile_enable(tables, 0, 0)
+
+    pairs_per_s = args.steps * B / elapsed
+    bpp = algorithmic_bytes_per_pair(d, K)
+    avg_kernel_ms = kern_ms / max(kern_n, 1)
+    achieved = (bpp * B) / (avg_kernel_ms * 1e-3) / 1e9 if kern_n else None
+    result = {
+        "metric": "positive edge samples/sec on 1 MI355X + achieved HBM GB/s vs peak",
+        "value": pairs_per_s,
+        "unit": "pairs/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": name, "nodes": V, "dim": d, "negatives": K, "batch": B, "block_grid": f"{grid}x{grid}",
+                   "end_to_end_GBps": pairs_per_s * bpp / 1e9},
+        "roofline": {"bound": "hbm", "kernel": "train_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
+                     "traffic": TRAFFIC_BYTES_PER_LAUNCH[name], "bytes_per_launch": bpp * B,
+                     "avg_kernel_ms": avg_kernel_ms, "kernel_samples": kern_n},
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, deg_host, bp, sched, args.cpu_batches)
+    print(json.dumps(result), flush=True)
+
+
+def cpu_baseline(w, deg_host, bp, sched, n_cpu_batches):
+    """The CPU oracle as it stands, timed on this host on a bounded sample of the same workload."""
+    import oracle
+    V, d, K, B, seed = w["V"], w["d"], w["K"], w["B"], w["seed"]
+    fold = min(V, 1_000_000)          # host tables of the 100 M-node cases do not fit: fold ids mod 1 M
+    X, C = oracle.init_tables(fold, d, seed)
+    if V == fold:
+        deg_fold = deg_host
+    else:
+        acc = np.zeros(fold, dtype=np.uint64)
+        np.add.at(acc, np.arange(V, dtype=np.int64) % fold, deg_host)
+        deg_fold = np.minimum(acc, 2**32 - 1).astype(np.uint32)
+    thr, alias, _ = oracle.build_alias(deg_fold)
+
+    def batch(i):
+        s, n, _, _ = sched[i % len(sched)]
+        p = bp.pairs[s:s + n].cpu().numpy()
+        return np.ascontiguousarray(p % fold if V != fold else p, dtype=np.int32)
+
+    def run(i, p):
+        neg = oracle.sample_negatives(seed, i * B, p.shape[0], K, thr, alias, 0)
+        oracle.train_batch(X, C, p, neg, 0.025)
+
+    p0 = batch(0)
+    t0 = time.perf_counter()
+    run(0, p0)
+    first = time.perf_counter() - t0
+    if n_cpu_batches <= 0:               # size the sample to about 15 s of oracle work
+        n_cpu_batches = int(max(1, min(256, 15.0 / max(first, 1e-3))))
+    batches = [batch(i) for i in range(1, n_cpu_batches + 1)]
+    t0 = time.perf_counter()
+    done = 0
+    for i, p in enumerate(batches, start=1):
+        run(i, p)
+        done += p.shape[0]
+    dt = time.perf_counter() - t0
+    sample = f"{n_cpu_batches} batches of {B} pairs"
+    if V != fold:
+        sample += f" on a row-folded replica (ids mod {fold})"
+    return {"value": done / dt, "unit": "pairs/s", "cores": 1, "kind": "oracle", "sample": sample,
+            "seconds": dt, "host_cpus": os.cpu_count()}
+
+
+if __name__ == "__main__":
+    main()

@@ -14,7 +14,8 @@
  *
  * Conventions
  *  - "_dev" pointers are device memory owned by the caller; "_host" pointers are host memory.  The
- *    library never allocates or frees device memory.  The opaque handles are small host structs.
+ *    library never allocates or frees device memory: scratch comes in as a workspace argument.
+ *    The opaque handles are small host structs.
  *  - hip_stream is a hipStream_t passed as void* (NULL = the default stream).  Unless stated
  *    otherwise a call enqueues its work on that stream and returns without synchronising.
  *  - Every call returns NE_OK or a negative ne_status.  Argument errors are detected on the host
@@ -44,7 +45,11 @@ typedef enum {
     NE_ERR_NOMEM = -4  /* host allocation failed                                                   */
 } ne_status;
 
-enum { NE_MAX_DIM = 1024, NE_MAX_NEGATIVES = 63 };
+enum { NE_MAX_DIM = 1024, NE_MAX_NEGATIVES = 62, NE_MAX_BATCH = 1 << 22 };
+
+/* Bytes of device workspace a tables handle needs to train batches of up to max_batch pairs with up
+ * to max_negatives negatives each (0 if an argument is invalid). */
+size_t ne_workspace_bytes(int32_t dim, int64_t max_batch, int32_t max_negatives);
 
 /*
  * Bind the vertex and context embedding matrices of Sec. II-A ("Embedding Representation") and,
@@ -55,10 +60,17 @@ enum { NE_MAX_DIM = 1024, NE_MAX_NEGATIVES = 63 };
  *                             must stay valid while the handle is used.
  *   0 < num_nodes < 2^31;  dim % 4 == 0, 4 <= dim <= NE_MAX_DIM.
  *   seed keys every random draw made through this handle.
+ *   workspace_dev : device scratch for ne_train_batch, 256-byte aligned, at least
+ *                   ne_workspace_bytes(dim, max_batch, max_negatives) bytes, caller-owned, used only
+ *                   through this handle until the handle is destroyed; it is cleared on the stream
+ *                   here.  Pass NULL with max_batch = 0 for a handle that is only evaluated.
+ *   1 <= max_batch <= NE_MAX_BATCH, 0 <= max_negatives <= NE_MAX_NEGATIVES when training.
  * *out receives a handle to free with ne_destroy_tables.  Errors: NE_ERR_ARG, NE_ERR_NOMEM, NE_ERR_HIP.
  */
 ne_status ne_create_tables(ne_tables** out, int64_t num_nodes, int32_t dim, float* vertex_dev,
-                           float* context_dev, uint64_t seed, int32_t init, void* hip_stream);
+                           float* context_dev, uint64_t seed, int32_t init, int64_t max_batch,
+                           int32_t max_negatives, void* workspace_dev, size_t workspace_bytes,
+                           void* hip_stream);
 
 /*
  * Build the negative-sampling table (Algorithm 1, NegativeSample) for the id range [base, base+n):
@@ -75,29 +87,26 @@ ne_status ne_create_tables(ne_tables** out, int64_t num_nodes, int32_t dim, floa
 ne_status ne_build_neg_alias(ne_alias** out, const uint32_t* degree_host, int64_t n, int32_t base,
                              void* alias_dev, void* hip_stream);
 
-/* Bytes of device scratch ne_train_batch needs for a batch of B pairs (0 if an argument is invalid). */
-size_t ne_staging_bytes(int64_t B, int32_t dim, int32_t K);
-
 /*
  * One minibatch-synchronous SGNS step (Algorithm 1, one iteration of the embedding-training loop
  * for every pair of the batch).
  *   pairs_dev   : device, int32[B][2] = (src, ctx), 8-byte aligned; ids must lie in [0, num_nodes).
- *   K           : negatives per pair, 0 <= K <= NE_MAX_NEGATIVES.  Negative k of pair b is the alias
- *                 draw for Philox(key = seed, counter = (idx_lo, idx_hi, k, 0)), idx = sample_base + b.
- *                 The alias range must lie inside [0, num_nodes).
+ *   B           : 0 <= B <= max_batch of the handle.  B == 0 is a no-op.
+ *   K           : negatives per pair, 0 <= K <= max_negatives of the handle.  Negative k of pair b is
+ *                 the alias draw for Philox(key = seed, counter = (idx_lo, idx_hi, k, 0)),
+ *                 idx = sample_base + b.  The alias range must lie inside [0, num_nodes).
  *   lr          : learning rate of this batch (the caller owns the schedule).
- *   staging_dev : device scratch of at least ne_staging_bytes(B, dim, K) bytes, 16-byte aligned;
- *                 contents are overwritten.  staging_bytes is its size.
  *   neg_out_dev : NULL, or device int32[B][K] that receives the negative ids used.
  * With x = vertex[src], c_0 = context[ctx], c_k = context[neg_k] read before the batch:
  *   s_j = <x, c_j>,  g_0 = 1 - sigmoid(s_0),  g_k = -sigmoid(s_k),
- *   vertex[src] += lr * sum_j g_j c_j,   context[id_j] += lr * g_j x   (fp32 atomic adds).
- * B == 0 is a no-op.  Calls on one pair of tables must be ordered by the stream.
- * Errors: NE_ERR_ARG, NE_ERR_STATE, NE_ERR_HIP.
+ *   vertex[src] += lr * sum_j g_j c_j,   context[id_j] += lr * g_j x,
+ * contributions to the same row summed (in fp32; the order of the sum is not fixed).
+ * Calls on one handle must be ordered by the stream and must not overlap: the handle's workspace
+ * carries state from one call to the next.  Errors: NE_ERR_ARG, NE_ERR_STATE, NE_ERR_HIP.
  */
 ne_status ne_train_batch(ne_tables* tables, const ne_alias* alias, const int32_t* pairs_dev, int64_t B,
-                         int32_t K, float lr, uint64_t sample_base, void* staging_dev,
-                         size_t staging_bytes, int32_t* neg_out_dev, void* hip_stream);
+                         int32_t K, float lr, uint64_t sample_base, int32_t* neg_out_dev,
+                         void* hip_stream);
 
 /*
  * Loss of a batch at the current tables with the same negatives ne_train_batch would draw; nothing
@@ -117,6 +126,17 @@ ne_status ne_eval_loss(const ne_tables* tables, const ne_alias* alias, const int
  */
 ne_status ne_validate_pairs(const ne_tables* tables, const int32_t* pairs_dev, int64_t B,
                             unsigned long long* bad_count_dev, void* hip_stream);
+
+/*
+ * Measurement hooks (instrumentation for benchmarks, not part of the method).  After
+ * ne_profile_enable(t, n, max_samples) with n > 0, every n-th ne_train_batch call records a HIP event
+ * on the stream immediately before and after its train kernel (the kernel that gathers the rows,
+ * scores and writes them back), for at most max_samples (<= 65536) calls; n = 0 switches it off.
+ * ne_profile_read waits for the recorded events, stores the sum of the kernel durations in
+ * milliseconds in *total_ms_host and their number in *samples_host (both host), and starts over.
+ */
+ne_status ne_profile_enable(ne_tables* tables, int32_t every_n, int32_t max_samples);
+ne_status ne_profile_read(ne_tables* tables, double* total_ms_host, int64_t* samples_host);
 
 void ne_destroy_tables(ne_tables* tables);
 void ne_destroy_alias(ne_alias* alias);

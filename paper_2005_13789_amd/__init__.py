@@ -21,11 +21,12 @@ NE_ERR_STATE = -2
 NE_ERR_HIP = -3
 NE_ERR_NOMEM = -4
 NE_MAX_DIM = 1024
-NE_MAX_NEGATIVES = 63
+NE_MAX_NEGATIVES = 62
+NE_MAX_BATCH = 1 << 22
 
 EXPORTS = (
-    "ne_create_tables", "ne_build_neg_alias", "ne_staging_bytes", "ne_train_batch", "ne_eval_loss",
-    "ne_validate_pairs", "ne_destroy_tables", "ne_destroy_alias", "ne_last_error",
+    "ne_create_tables", "ne_build_neg_alias", "ne_workspace_bytes", "ne_train_batch", "ne_eval_loss",
+    "ne_validate_pairs", "ne_profile_enable", "ne_profile_read", "ne_destroy_tables", "ne_destroy_alias", "ne_last_error",
 )
 
 _lib = None
@@ -48,18 +49,23 @@ def lib() -> ctypes.CDLL:
     L = ctypes.CDLL(LIB_PATH)
     c = ctypes
     vp = c.c_void_p
-    L.ne_create_tables.argtypes = [c.POINTER(vp), c.c_int64, c.c_int32, vp, vp, c.c_uint64, c.c_int32, vp]
+    L.ne_create_tables.argtypes = [c.POINTER(vp), c.c_int64, c.c_int32, vp, vp, c.c_uint64, c.c_int32, c.c_int64,
+                                   c.c_int32, vp, c.c_size_t, vp]
     L.ne_create_tables.restype = c.c_int
     L.ne_build_neg_alias.argtypes = [c.POINTER(vp), vp, c.c_int64, c.c_int32, vp, vp]
     L.ne_build_neg_alias.restype = c.c_int
-    L.ne_staging_bytes.argtypes = [c.c_int64, c.c_int32, c.c_int32]
-    L.ne_staging_bytes.restype = c.c_size_t
-    L.ne_train_batch.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_float, c.c_uint64, vp, c.c_size_t, vp, vp]
+    L.ne_workspace_bytes.argtypes = [c.c_int32, c.c_int64, c.c_int32]
+    L.ne_workspace_bytes.restype = c.c_size_t
+    L.ne_train_batch.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_float, c.c_uint64, vp, vp]
     L.ne_train_batch.restype = c.c_int
     L.ne_eval_loss.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_uint64, vp, vp, vp]
     L.ne_eval_loss.restype = c.c_int
     L.ne_validate_pairs.argtypes = [vp, vp, c.c_int64, vp, vp]
     L.ne_validate_pairs.restype = c.c_int
+    L.ne_profile_enable.argtypes = [vp, c.c_int32, c.c_int32]
+    L.ne_profile_enable.restype = c.c_int
+    L.ne_profile_read.argtypes = [vp, c.POINTER(c.c_double), c.POINTER(c.c_int64)]
+    L.ne_profile_read.restype = c.c_int
     L.ne_destroy_tables.argtypes = [vp]
     L.ne_destroy_tables.restype = None
     L.ne_destroy_alias.argtypes = [vp]
@@ -90,13 +96,14 @@ def _dev_ptr(t, dtype, name: str) -> int:
 
 
 class Tables:
-    """Handle from ne_create_tables; keeps the two table tensors alive."""
+    """Handle from ne_create_tables; keeps the table and workspace tensors alive."""
 
-    def __init__(self, handle: int, vertex: torch.Tensor, context: torch.Tensor, seed: int):
+    def __init__(self, handle: int, vertex: torch.Tensor, context: torch.Tensor, seed: int, workspace):
         self.handle = handle
         self.vertex = vertex
         self.context = context
         self.seed = seed
+        self.workspace = workspace
         self.num_nodes, self.dim = vertex.shape
 
     def __del__(self):
@@ -120,17 +127,28 @@ class Alias:
             self.handle = None
 
 
+def ne_workspace_bytes(dim: int, max_batch: int, max_negatives: int) -> int:
+    return int(lib().ne_workspace_bytes(dim, max_batch, max_negatives))
+
+
 def ne_create_tables(vertex: torch.Tensor, context: torch.Tensor, seed: int, init: bool = True,
+                     max_batch: int = 0, max_negatives: int = 0, workspace: torch.Tensor | None = None,
                      stream=None) -> Tables:
-    """Bind fp32 [num_nodes][dim] CUDA tensors; if init, vertex ~ U(-0.5/dim, 0.5/dim), context = 0."""
+    """Bind fp32 [num_nodes][dim] CUDA tensors; if init, vertex ~ U(-0.5/dim, 0.5/dim), context = 0.
+
+    workspace: CUDA uint8 tensor of ne_workspace_bytes(dim, max_batch, max_negatives) bytes (needed
+    for ne_train_batch; leave None with max_batch = 0 for an evaluate-only handle).
+    """
     vp = _dev_ptr(vertex, torch.float32, "vertex")
     cp = _dev_ptr(context, torch.float32, "context")
     if vertex.dim() != 2 or vertex.shape != context.shape:
         raise TypeError("vertex and context must both be [num_nodes][dim]")
+    wp = _dev_ptr(workspace, torch.uint8, "workspace")
     out = ctypes.c_void_p()
     _check(lib().ne_create_tables(ctypes.byref(out), vertex.shape[0], vertex.shape[1], vp, cp,
-                                  seed & (2**64 - 1), 1 if init else 0, _stream_ptr(stream)))
-    return Tables(out.value, vertex, context, seed)
+                                  seed & (2**64 - 1), 1 if init else 0, max_batch, max_negatives, wp,
+                                  workspace.numel() if workspace is not None else 0, _stream_ptr(stream)))
+    return Tables(out.value, vertex, context, seed, workspace)
 
 
 def ne_build_neg_alias(degree_host, base: int, alias_table: torch.Tensor, stream=None) -> Alias:
@@ -148,23 +166,18 @@ def ne_build_neg_alias(degree_host, base: int, alias_table: torch.Tensor, stream
     return Alias(out.value, alias_table, n, base)
 
 
-def ne_staging_bytes(B: int, dim: int, K: int) -> int:
-    return int(lib().ne_staging_bytes(B, dim, K))
-
-
 def ne_train_batch(tables: Tables, alias: Alias | None, pairs: torch.Tensor, K: int, lr: float,
-                   sample_base: int, staging: torch.Tensor, neg_out: torch.Tensor | None = None,
-                   stream=None, B: int | None = None) -> None:
+                   sample_base: int, neg_out: torch.Tensor | None = None, stream=None,
+                   B: int | None = None) -> None:
     """One minibatch-synchronous SGNS step on pairs int32 [B][2] (CUDA)."""
     if B is None:
         B = int(pairs.shape[0])
     pp = _dev_ptr(pairs, torch.int32, "pairs")
-    sp = _dev_ptr(staging, torch.uint8, "staging")
     np_ = _dev_ptr(neg_out, torch.int32, "neg_out")
     if neg_out is not None and neg_out.numel() < B * K:
         raise TypeError("neg_out needs B*K int32 elements")
     _check(lib().ne_train_batch(tables.handle, alias.handle if alias else None, pp, B, K, lr, sample_base,
-                                sp, staging.numel(), np_, _stream_ptr(stream)))
+                                np_, _stream_ptr(stream)))
 
 
 def ne_eval_loss(tables: Tables, alias: Alias | None, pairs: torch.Tensor, K: int, sample_base: int,
@@ -187,6 +200,19 @@ def ne_validate_pairs(tables: Tables, pairs: torch.Tensor, bad_count: torch.Tens
     pp = _dev_ptr(pairs, torch.int32, "pairs")
     bp = _dev_ptr(bad_count, torch.int64, "bad_count")
     _check(lib().ne_validate_pairs(tables.handle, pp, int(pairs.shape[0]), bp, _stream_ptr(stream)))
+
+
+def ne_profile_enable(tables: Tables, every_n: int, max_samples: int = 4096) -> None:
+    """Record HIP events around the train kernel of every n-th ne_train_batch call (0 = off)."""
+    _check(lib().ne_profile_enable(tables.handle, every_n, max_samples))
+
+
+def ne_profile_read(tables: Tables):
+    """(sum of the sampled train-kernel durations in ms, number of samples); resets the samples."""
+    total = ctypes.c_double()
+    n = ctypes.c_int64()
+    _check(lib().ne_profile_read(tables.handle, ctypes.byref(total), ctypes.byref(n)))
+    return total.value, n.value
 
 
 def ne_last_error() -> str:

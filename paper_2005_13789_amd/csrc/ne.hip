@@ -1,14 +1,23 @@
 // SGNS node-embedding training for MI355X (gfx950): HIP kernels and the C ABI declared in ne.h.
 //
-// Kernel plan for one batch (Algorithm 1, embedding-training loop; Sec. II-A "Training Process"):
-//   score  : one lane group per (src, ctx) pair.  Draws the K negatives (Philox + alias table),
-//            gathers x = vertex[src] and the K+1 context rows with dwordx4 loads, reduces the K+1 dot
-//            products across the group with DPP, forms g_j and dx = lr * sum_j g_j c_j.  Tables are
-//            read-only here.  x, dx, lr*g_j and the ids go to a staging buffer.
-//   update : one lane group per pair.  Reads the staged x, dx, g, ids and scatter-adds
-//            vertex[src] += dx and context[id_j] += (lr g_j) x with hardware fp32 atomics.
-// The kernel boundary between the two is what makes the step minibatch-synchronous: no table row is
-// written before every read of the batch has completed.
+// One batch of the embedding-training loop (Algorithm 1; Sec. II-A "Training Process") is three
+// kernels on the caller's stream:
+//
+//   prep   (ids only)  one thread per row reference (src, ctx, K negatives of every pair): draws the
+//          negative (Philox + alias table), inserts (table, row) into a batch-local hash set and
+//          learns whether another reference of the batch names the same row.  Rows named at least
+//          twice are "shared"; each gets the hash position as its delta slot.
+//   train  one lane group per pair: gathers x = vertex[src] and the K+1 context rows (dwordx4),
+//          reduces the K+1 dot products with DPP, forms g_j and the deltas.  A row that only this
+//          pair names is rewritten in place from registers (old + delta, one plain store: every row
+//          costs one read and one write).  A shared row is left untouched - other pairs must still
+//          read its pre-batch value - and its delta is added to the row's slot with fp32 atomics.
+//   apply  adds each slot to its table row, zeroes the slot and empties the hash set.
+//
+// This is exactly minibatch-synchronous: no row that a second reference could read is written
+// before the apply kernel, and all contributions to a row are summed.  fp32 atomics on gfx950
+// retire one dword per L2 channel clock, far below the rate of plain row stores, which is why only
+// shared rows go through them.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -23,7 +32,7 @@
 #include "ne.h"
 
 // ---------------------------------------------------------------------------------------------
-// host-side error plumbing
+// host-side error plumbing and handles
 // ---------------------------------------------------------------------------------------------
 static thread_local std::string g_last_error;
 
@@ -40,12 +49,37 @@ static ne_status fail(ne_status st, const std::string& msg)
             return fail(NE_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));          \
     } while (0)
 
+namespace {
+
+// Device workspace of a tables handle (caller's memory, carved up here).
+struct Workspace {
+    uint32_t* keys;      // [cap]     hash set of (table bit << 31 | row); 0xFFFFFFFF = empty
+    uint32_t* dupbits;   // [cap/32]  bit pos set <=> the row at keys[pos] is shared
+    uint32_t* counters;  // [4]       [0],[1]: number of shared rows of the even / odd batch
+    uint2* dup_list;     // [cap/4]   (pos, key) of every shared row of the batch
+    int32_t* ids;        // [max_B][max_K+2]  src, ctx, negatives
+    uint32_t* posbuf;    // [max_B][max_K+2]  hash position of each reference
+    float* delta;        // [cap][dim]        per-slot fp32 accumulators, zero between batches
+    uint32_t cap;        // power of two >= 2 * max_B * (max_K + 2)
+    size_t total_bytes;
+};
+
+}  // namespace
+
 struct ne_tables {
     int64_t num_nodes;
     int32_t dim;
     float* vertex;
     float* context;
     uint64_t seed;
+    int64_t max_batch;
+    int32_t max_negatives;
+    Workspace ws;
+    uint64_t batches_done;   // parity selects the shared-row counter
+    // optional timing of the train kernel with HIP events (ne_profile_enable / ne_profile_read)
+    int32_t profile_every;
+    std::vector<hipEvent_t> ev_start, ev_stop;
+    size_t ev_used;
 };
 
 struct ne_alias {
@@ -60,6 +94,7 @@ struct ne_alias {
 namespace {
 
 enum : uint32_t { kStreamNegative = 0, kStreamInit = 1, kStreamSharedNegative = 2 };
+constexpr uint32_t kEmptyKey = 0xFFFFFFFFu;
 
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11).
 __device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint32_t k0, uint32_t k1)
@@ -84,6 +119,14 @@ __device__ __forceinline__ int32_t alias_draw(uint4 r, const uint2* __restrict__
     const uint64_t slot = __umul64hi(u, n);
     const uint2 e = table[slot];
     return static_cast<int32_t>(r.z < e.x ? static_cast<uint32_t>(slot) : e.y);
+}
+
+__device__ __forceinline__ int32_t draw_negative(uint64_t sample, uint32_t k, uint32_t k0, uint32_t k1,
+                                                 const uint2* __restrict__ table, uint64_t n, int32_t base)
+{
+    const uint4 r = philox4x32_10(make_uint4(static_cast<uint32_t>(sample), static_cast<uint32_t>(sample >> 32), k,
+                                             kStreamNegative), k0, k1);
+    return base + alias_draw(r, table, n);
 }
 
 template <int CTRL>
@@ -116,6 +159,20 @@ __device__ __forceinline__ float dot4(float4 a, float4 b)
     return fmaf(a.x, b.x, fmaf(a.y, b.y, fmaf(a.z, b.z, a.w * b.w)));
 }
 
+__device__ __forceinline__ float4 axpy4(float g, float4 x, float4 y)
+{
+    return make_float4(fmaf(g, x.x, y.x), fmaf(g, x.y, y.y), fmaf(g, x.z, y.z), fmaf(g, x.w, y.w));
+}
+
+// ---------------------------------------------------------------------------------------------
+// small fills (hipMemsetAsync is avoided so that callers may capture the stream)
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* __restrict__ p, size_t n, uint32_t v)
+{
+    const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
+    for (size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = v;
+}
+
 // ---------------------------------------------------------------------------------------------
 // table initialisation: vertex ~ U(-0.5/d, 0.5/d), context = 0.  One float4 per thread-iteration.
 // ---------------------------------------------------------------------------------------------
@@ -141,81 +198,148 @@ __global__ __launch_bounds__(256) void init_tables_kernel(float4* __restrict__ X
 }
 
 // ---------------------------------------------------------------------------------------------
-// score kernel.  G lanes per pair, NCH float4 chunks per lane (chunk index = lg + i*G, valid while
-// < d4), JB context rows in flight at a time.  TRAIN: writes staging.  !TRAIN: accumulates the loss.
+// prep kernel: one thread per row reference.  Reference j of pair b: j = 0 the source row (vertex
+// table), j = 1 the positive context row, j = 2.. negative j-2 (context table).
 // ---------------------------------------------------------------------------------------------
-struct ScoreArgs {
-    const float4* X;
-    const float4* C;
+struct PrepArgs {
     const int2* pairs;
     int64_t B;
     int32_t K;
-    int32_t d4;
-    float lr;
     uint64_t sample_base;
     uint32_t k0, k1;
     const uint2* alias;
     uint64_t alias_n;
     int32_t alias_base;
-    float* gbuf;      // [B][K+1]  lr * g_j
-    int32_t* nbuf;    // [B][K]    negative ids
-    float4* xbuf;     // [B][d4]   copy of x
-    float4* dxbuf;    // [B][d4]   lr * sum_j g_j c_j
-    int32_t* neg_out; // optional [B][K]
-    double* loss;     // eval only
+    uint32_t* keys;
+    uint32_t mask;        // cap - 1
+    uint32_t* dupbits;
+    uint32_t* n_dup;
+    uint2* dup_list;
+    int32_t* ids;
+    uint32_t* posbuf;
+    int32_t* neg_out;
 };
 
-template <int G, int NCH, int JB, bool TRAIN>
-__global__ __launch_bounds__(256) void score_kernel(ScoreArgs a)
+__global__ __launch_bounds__(256) void prep_kernel(PrepArgs a)
 {
-    constexpr int GROUPS = 256 / G;
-    const int lg = threadIdx.x & (G - 1);
-    const int64_t b_raw = static_cast<int64_t>(blockIdx.x) * GROUPS + (threadIdx.x / G);
-    const bool active = b_raw < a.B;
-    const int64_t b = active ? b_raw : a.B - 1;
-    const int K = a.K;
-    const int d4 = a.d4;
-
-    const int2 pr = a.pairs[b];
-
-    // lane lg owns row j = lg of the pair: j = 0 the positive context, j = 1..K negative j-1
-    int32_t id_mine = pr.y;
-    if (lg >= 1 && lg <= K) {
-        const uint64_t idx = a.sample_base + static_cast<uint64_t>(b);
-        const uint4 r = philox4x32_10(make_uint4(static_cast<uint32_t>(idx), static_cast<uint32_t>(idx >> 32),
-                                                 static_cast<uint32_t>(lg - 1), kStreamNegative), a.k0, a.k1);
-        id_mine = a.alias_base + alias_draw(r, a.alias, a.alias_n);
-        if (active) {
-            if (TRAIN) a.nbuf[b * K + (lg - 1)] = id_mine;
-            if (a.neg_out) a.neg_out[b * K + (lg - 1)] = id_mine;
+    const int R = a.K + 2;
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (t >= a.B * R) return;
+    const int64_t b = t / R;
+    const int j = static_cast<int>(t - b * R);
+    int32_t id;
+    if (j < 2) {
+        const int2 pr = a.pairs[b];
+        id = j == 0 ? pr.x : pr.y;
+    } else {
+        id = draw_negative(a.sample_base + static_cast<uint64_t>(b), static_cast<uint32_t>(j - 2), a.k0, a.k1, a.alias,
+                           a.alias_n, a.alias_base);
+        if (a.neg_out) a.neg_out[b * a.K + (j - 2)] = id;
+    }
+    const uint32_t key = static_cast<uint32_t>(id) | (j == 0 ? 0u : 0x80000000u);
+    uint32_t pos = (key * 0x9E3779B1u) >> 7 & a.mask;
+    bool existed;
+    // the set holds at most cap/2 keys, so an empty position is always reached
+    while (true) {
+        const uint32_t prev = atomicCAS(&a.keys[pos], kEmptyKey, key);
+        if (prev == kEmptyKey) { existed = false; break; }
+        if (prev == key) { existed = true; break; }
+        pos = (pos + 1) & a.mask;
+    }
+    a.ids[t] = id;
+    a.posbuf[t] = pos;
+    if (existed) {
+        const uint32_t bit = 1u << (pos & 31);
+        const uint32_t old = atomicOr(&a.dupbits[pos >> 5], bit);
+        if (!(old & bit)) {
+            const uint32_t slot = atomicAdd(a.n_dup, 1u);
+            a.dup_list[slot] = make_uint2(pos, key);
         }
     }
+}
 
+// ---------------------------------------------------------------------------------------------
+// train kernel.  G lanes per pair, NCH float4 chunks per lane (chunk index = lg + i*G, valid while
+// < d4), JB context rows in flight at a time.
+// ---------------------------------------------------------------------------------------------
+struct TrainArgs {
+    float4* X;
+    float4* C;
+    int64_t B;
+    int32_t K;
+    int32_t d4;
+    float lr;
+    const int32_t* ids;
+    const uint32_t* posbuf;
+    const uint32_t* dupbits;
+    float* delta;
+};
+
+// Element e = lg + m*G of a row, for m < 4*NCH: the layout in which one atomic instruction of a lane
+// group covers consecutive dwords.  The float4-chunk layout is turned into it through LDS.
+template <int G, int NCH>
+__device__ __forceinline__ void to_consecutive(const float4 (&v)[NCH], float (&out)[4 * NCH], float* lds_row, int lg)
+{
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) reinterpret_cast<float4*>(lds_row)[lg + i * G] = v[i];
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int m = 0; m < 4 * NCH; ++m) out[m] = lds_row[lg + m * G];
+    __builtin_amdgcn_wave_barrier();
+}
+
+template <int G, int NCH, int JB>
+__global__ __launch_bounds__(256) void train_kernel(TrainArgs a)
+{
+    constexpr int GROUPS = 256 / G;
+    __shared__ float lds[GROUPS][4 * G * NCH];
+    const int lg = threadIdx.x & (G - 1);
+    const int grp = threadIdx.x / G;
+    const int64_t b = static_cast<int64_t>(blockIdx.x) * GROUPS + grp;
+    if (b >= a.B) return;   // whole groups leave together; groups never communicate below
+    const int K = a.K;
+    const int R = K + 2;
+    const int d4 = a.d4;
+    const int d = d4 * 4;
+
+    // lane j < R owns reference j: id, delta slot, shared flag
+    int32_t id_mine = 0;
+    uint32_t pos_mine = 0;
+    int shared_mine = 0;
+    if (lg < R) {
+        id_mine = a.ids[b * R + lg];
+        pos_mine = a.posbuf[b * R + lg];
+        shared_mine = (a.dupbits[pos_mine >> 5] >> (pos_mine & 31)) & 1;
+    }
+
+    const int32_t src = __shfl(id_mine, 0, G);
+    float4* xrow = a.X + static_cast<int64_t>(src) * d4;
     float4 xr[NCH];
-    const float4* xrow = a.X + static_cast<int64_t>(pr.x) * d4;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
         const int ci = lg + i * G;
         xr[i] = (ci < d4) ? xrow[ci] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
+    float xt[4 * NCH];   // x in consecutive-dword layout, for the atomic path
+    to_consecutive<G, NCH>(xr, xt, lds[grp], lg);
 
     float4 dx[NCH];
 #pragma unroll
     for (int i = 0; i < NCH; ++i) dx[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-    float g_mine = 0.0f;   // lane lg keeps lr*g_lg (TRAIN) or its loss term (eval)
 
     for (int j0 = 0; j0 <= K; j0 += JB) {
         float4 cr[JB][NCH];
         float part[JB];
+        float4* crow[JB];
 #pragma unroll
         for (int jj = 0; jj < JB; ++jj) {
             const int j = j0 + jj;
-            const int32_t id = __shfl(id_mine, j <= K ? j : K, G);
-            const float4* crow = a.C + static_cast<int64_t>(id) * d4;
+            const int32_t id = __shfl(id_mine, (j <= K ? j : K) + 1, G);
+            crow[jj] = a.C + static_cast<int64_t>(id) * d4;
 #pragma unroll
             for (int i = 0; i < NCH; ++i) {
                 const int ci = lg + i * G;
-                cr[jj][i] = (j <= K && ci < d4) ? crow[ci] : make_float4(0.f, 0.f, 0.f, 0.f);
+                cr[jj][i] = (j <= K && ci < d4) ? crow[jj][ci] : make_float4(0.f, 0.f, 0.f, 0.f);
             }
         }
 #pragma unroll
@@ -231,122 +355,168 @@ __global__ __launch_bounds__(256) void score_kernel(ScoreArgs a)
         for (int jj = 0; jj < JB; ++jj) {
             const int j = j0 + jj;
             if (j <= K) {
-                const float s = part[jj];
-                if (TRAIN) {
-                    const float sg = sigmoidf(s);
-                    const float g = a.lr * (j == 0 ? 1.0f - sg : -sg);
+                const float sg = sigmoidf(part[jj]);
+                const float g = a.lr * (j == 0 ? 1.0f - sg : -sg);
+                const int shared = __shfl(shared_mine, j + 1, G);
+                const uint32_t pos = __shfl(pos_mine, j + 1, G);
+#pragma unroll
+                for (int i = 0; i < NCH; ++i) dx[i] = axpy4(g, cr[jj][i], dx[i]);
+                if (!shared) {
 #pragma unroll
                     for (int i = 0; i < NCH; ++i) {
-                        dx[i].x = fmaf(g, cr[jj][i].x, dx[i].x);
-                        dx[i].y = fmaf(g, cr[jj][i].y, dx[i].y);
-                        dx[i].z = fmaf(g, cr[jj][i].z, dx[i].z);
-                        dx[i].w = fmaf(g, cr[jj][i].w, dx[i].w);
+                        const int ci = lg + i * G;
+                        if (ci < d4) crow[jj][ci] = axpy4(g, xr[i], cr[jj][i]);
                     }
-                    if (lg == j) g_mine = g;
                 } else {
-                    if (lg == j) g_mine = softplusf(j == 0 ? -s : s);
+                    float* slot = a.delta + static_cast<int64_t>(pos) * d;
+#pragma unroll
+                    for (int m = 0; m < 4 * NCH; ++m) {
+                        const int e = lg + m * G;
+                        if (e < d) unsafeAtomicAdd(slot + e, g * xt[m]);
+                    }
                 }
             }
         }
     }
 
-    if (TRAIN) {
-        if (active) {
-            if (lg <= K) a.gbuf[b * (K + 1) + lg] = g_mine;
-            float4* xo = a.xbuf + b * d4;
-            float4* dxo = a.dxbuf + b * d4;
-#pragma unroll
-            for (int i = 0; i < NCH; ++i) {
-                const int ci = lg + i * G;
-                if (ci < d4) {
-                    xo[ci] = xr[i];
-                    dxo[ci] = dx[i];
-                }
-            }
-        }
-    } else {
-        // per-pair loss = sum of the K+1 terms held by lanes 0..K; then block sum in fp64
-        float l = (active && lg <= K) ? g_mine : 0.0f;
-        l = group_sum<G>(l);
-        __shared__ double sh[GROUPS];
-        if (lg == 0) sh[threadIdx.x / G] = static_cast<double>(l);
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            double t = 0.0;
-            for (int i = 0; i < GROUPS; ++i) t += sh[i];
-            atomicAdd(a.loss, t);
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// update kernel: scatter-add of the staged deltas with hardware fp32 atomics.
-// ---------------------------------------------------------------------------------------------
-struct UpdateArgs {
-    float* X;
-    float* C;
-    const int2* pairs;
-    int64_t B;
-    int32_t K;
-    int32_t d4;
-    const float* gbuf;
-    const int32_t* nbuf;
-    const float4* xbuf;
-    const float4* dxbuf;
-};
-
-__device__ __forceinline__ void atomic_add4(float* p, float4 v)
-{
-    unsafeAtomicAdd(p + 0, v.x);
-    unsafeAtomicAdd(p + 1, v.y);
-    unsafeAtomicAdd(p + 2, v.z);
-    unsafeAtomicAdd(p + 3, v.w);
-}
-
-template <int G, int NCH>
-__global__ __launch_bounds__(256) void update_kernel(UpdateArgs a)
-{
-    constexpr int GROUPS = 256 / G;
-    const int lg = threadIdx.x & (G - 1);
-    const int64_t b = static_cast<int64_t>(blockIdx.x) * GROUPS + (threadIdx.x / G);
-    if (b >= a.B) return;   // whole groups leave together; no cross-group communication below
-    const int K = a.K;
-    const int d4 = a.d4;
-    const int2 pr = a.pairs[b];
-
-    int32_t id_mine = pr.y;
-    float g_mine = 0.0f;
-    if (lg <= K) {
-        g_mine = a.gbuf[b * (K + 1) + lg];
-        if (lg >= 1) id_mine = a.nbuf[b * K + (lg - 1)];
-    }
-    float4 xr[NCH], dx[NCH];
-    const float4* xi = a.xbuf + b * d4;
-    const float4* dxi = a.dxbuf + b * d4;
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-        const int ci = lg + i * G;
-        if (ci < d4) {
-            xr[i] = xi[ci];
-            dx[i] = dxi[ci];
-        }
-    }
-    float* xrow = a.X + static_cast<int64_t>(pr.x) * d4 * 4;
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-        const int ci = lg + i * G;
-        if (ci < d4) atomic_add4(xrow + 4 * ci, dx[i]);
-    }
-    for (int j = 0; j <= K; ++j) {
-        const int32_t id = __shfl(id_mine, j, G);
-        const float g = __shfl(g_mine, j, G);
-        float* crow = a.C + static_cast<int64_t>(id) * d4 * 4;
+    const int shared0 = __shfl(shared_mine, 0, G);
+    const uint32_t pos0 = __shfl(pos_mine, 0, G);
+    if (!shared0) {
 #pragma unroll
         for (int i = 0; i < NCH; ++i) {
             const int ci = lg + i * G;
             if (ci < d4)
-                atomic_add4(crow + 4 * ci, make_float4(g * xr[i].x, g * xr[i].y, g * xr[i].z, g * xr[i].w));
+                xrow[ci] = make_float4(xr[i].x + dx[i].x, xr[i].y + dx[i].y, xr[i].z + dx[i].z, xr[i].w + dx[i].w);
         }
+    } else {
+        float dxt[4 * NCH];
+        to_consecutive<G, NCH>(dx, dxt, lds[grp], lg);
+        float* slot = a.delta + static_cast<int64_t>(pos0) * d;
+#pragma unroll
+        for (int m = 0; m < 4 * NCH; ++m) {
+            const int e = lg + m * G;
+            if (e < d) unsafeAtomicAdd(slot + e, dxt[m]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// apply kernel: table[row] += slot, slot = 0 for every shared row; then empty the hash set.
+// 16 lanes per shared row, grid-stride over the list.
+// ---------------------------------------------------------------------------------------------
+struct ApplyArgs {
+    float4* X;
+    float4* C;
+    int32_t d4;
+    float4* delta;
+    const uint2* dup_list;
+    uint32_t* n_dup;        // this batch's count (read)
+    uint32_t* n_dup_next;   // next batch's count (reset to 0)
+    uint32_t* keys;
+    uint32_t* dupbits;
+    uint32_t cap;
+};
+
+__global__ __launch_bounds__(256) void apply_kernel(ApplyArgs a)
+{
+    const uint32_t n = *a.n_dup;
+    const int lg = threadIdx.x & 15;
+    const uint32_t groups_total = gridDim.x * 16u;
+    for (uint32_t i = blockIdx.x * 16u + (threadIdx.x >> 4); i < n; i += groups_total) {
+        const uint2 e = a.dup_list[i];
+        float4* row = ((e.y & 0x80000000u) ? a.C : a.X) + static_cast<int64_t>(e.y & 0x7FFFFFFFu) * a.d4;
+        float4* slot = a.delta + static_cast<int64_t>(e.x) * a.d4;
+        for (int ci = lg; ci < a.d4; ci += 16) {
+            const float4 v = slot[ci];
+            const float4 t = row[ci];
+            row[ci] = make_float4(t.x + v.x, t.y + v.y, t.z + v.z, t.w + v.w);
+            slot[ci] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+    const uint32_t stride = gridDim.x * 256u;
+    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < a.cap; i += stride) a.keys[i] = kEmptyKey;
+    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < a.cap / 32; i += stride) a.dupbits[i] = 0u;
+    if (blockIdx.x == 0 && threadIdx.x == 0) *a.n_dup_next = 0u;
+}
+
+// ---------------------------------------------------------------------------------------------
+// loss kernel (ne_eval_loss): sampling + scoring fused, tables read-only.
+// ---------------------------------------------------------------------------------------------
+struct LossArgs {
+    const float4* X;
+    const float4* C;
+    const int2* pairs;
+    int64_t B;
+    int32_t K;
+    int32_t d4;
+    uint64_t sample_base;
+    uint32_t k0, k1;
+    const uint2* alias;
+    uint64_t alias_n;
+    int32_t alias_base;
+    int32_t* neg_out;
+    double* loss;
+};
+
+template <int G, int NCH, int JB>
+__global__ __launch_bounds__(256) void loss_kernel(LossArgs a)
+{
+    constexpr int GROUPS = 256 / G;
+    const int lg = threadIdx.x & (G - 1);
+    const int64_t b_raw = static_cast<int64_t>(blockIdx.x) * GROUPS + (threadIdx.x / G);
+    const bool active = b_raw < a.B;
+    const int64_t b = active ? b_raw : a.B - 1;
+    const int K = a.K;
+    const int d4 = a.d4;
+    const int2 pr = a.pairs[b];
+
+    // lane lg owns context row j = lg of the pair: j = 0 the positive, j = 1..K negative j-1
+    int32_t id_mine = pr.y;
+    if (lg >= 1 && lg <= K) {
+        id_mine = draw_negative(a.sample_base + static_cast<uint64_t>(b), static_cast<uint32_t>(lg - 1), a.k0, a.k1,
+                                a.alias, a.alias_n, a.alias_base);
+        if (active && a.neg_out) a.neg_out[b * K + (lg - 1)] = id_mine;
+    }
+    float4 xr[NCH];
+    const float4* xrow = a.X + static_cast<int64_t>(pr.x) * d4;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int ci = lg + i * G;
+        xr[i] = (ci < d4) ? xrow[ci] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    float term_mine = 0.0f;   // lane j keeps the loss term of row j
+    for (int j0 = 0; j0 <= K; j0 += JB) {
+        float part[JB];
+#pragma unroll
+        for (int jj = 0; jj < JB; ++jj) {
+            const int j = j0 + jj;
+            const int32_t id = __shfl(id_mine, j <= K ? j : K, G);
+            const float4* crow = a.C + static_cast<int64_t>(id) * d4;
+            float p = 0.0f;
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) {
+                const int ci = lg + i * G;
+                if (j <= K && ci < d4) p += dot4(xr[i], crow[ci]);
+            }
+            part[jj] = p;
+        }
+#pragma unroll
+        for (int jj = 0; jj < JB; ++jj) part[jj] = group_sum<G>(part[jj]);
+#pragma unroll
+        for (int jj = 0; jj < JB; ++jj) {
+            const int j = j0 + jj;
+            if (j <= K && lg == j) term_mine = softplusf(j == 0 ? -part[jj] : part[jj]);
+        }
+    }
+    float l = (active && lg <= K) ? term_mine : 0.0f;
+    l = group_sum<G>(l);
+    __shared__ double sh[GROUPS];
+    if (lg == 0) sh[threadIdx.x / G] = static_cast<double>(l);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+        for (int i = 0; i < GROUPS; ++i) t += sh[i];
+        atomicAdd(a.loss, t);
     }
 }
 
@@ -367,73 +537,89 @@ __global__ __launch_bounds__(256) void validate_pairs_kernel(const int32_t* __re
 // ---------------------------------------------------------------------------------------------
 struct Shape { int G, NCH; };
 
-// Smallest lane group that covers dim/4 float4 chunks and has a lane for each of the K+1 rows.
+// Smallest lane group that covers dim/4 float4 chunks and has a lane for each of the K+2 references.
 bool pick_shape(int32_t d4, int32_t K, Shape* out)
 {
     static const Shape order[] = {{8, 1}, {16, 1}, {16, 2}, {32, 1}, {32, 2}, {64, 1}, {64, 2}, {64, 4}};
     for (const Shape& s : order) {
-        if (s.G * s.NCH >= d4 && s.G >= K + 1) { *out = s; return true; }
+        if (s.G * s.NCH >= d4 && s.G >= K + 2) { *out = s; return true; }
     }
     return false;
 }
 
-struct StagingLayout { size_t g_off, n_off, x_off, dx_off, total; };
+#define NE_FOR_EACH_SHAPE(M) M(8, 1) M(16, 1) M(16, 2) M(32, 1) M(32, 2) M(64, 1) M(64, 2) M(64, 4)
 
-StagingLayout staging_layout(int64_t B, int32_t dim, int32_t K)
-{
-    auto up = [](size_t v) { return (v + 255) & ~static_cast<size_t>(255); };
-    StagingLayout L;
-    size_t off = 0;
-    L.g_off = off;  off = up(off + static_cast<size_t>(B) * (K + 1) * sizeof(float));
-    L.n_off = off;  off = up(off + static_cast<size_t>(B) * (K > 0 ? K : 1) * sizeof(int32_t));
-    L.x_off = off;  off = up(off + static_cast<size_t>(B) * dim * sizeof(float));
-    L.dx_off = off; off = up(off + static_cast<size_t>(B) * dim * sizeof(float));
-    L.total = off;
-    return L;
-}
-
-template <bool TRAIN>
-hipError_t launch_score(const Shape& s, const ScoreArgs& a, hipStream_t st)
+hipError_t launch_train(const Shape& s, const TrainArgs& a, hipStream_t st)
 {
     const int groups = 256 / s.G;
     const unsigned grid = static_cast<unsigned>((a.B + groups - 1) / groups);
-#define NE_SCORE_CASE(G_, N_)                                                                    \
+#define NE_CASE(G_, N_)                                                                          \
     if (s.G == G_ && s.NCH == N_) {                                                              \
-        hipLaunchKernelGGL((score_kernel<G_, N_, 6, TRAIN>), dim3(grid), dim3(256), 0, st, a);   \
+        hipLaunchKernelGGL((train_kernel<G_, N_, 6>), dim3(grid), dim3(256), 0, st, a);          \
         return hipGetLastError();                                                                \
     }
-    NE_SCORE_CASE(8, 1) NE_SCORE_CASE(16, 1) NE_SCORE_CASE(16, 2) NE_SCORE_CASE(32, 1)
-    NE_SCORE_CASE(32, 2) NE_SCORE_CASE(64, 1) NE_SCORE_CASE(64, 2) NE_SCORE_CASE(64, 4)
-#undef NE_SCORE_CASE
+    NE_FOR_EACH_SHAPE(NE_CASE)
+#undef NE_CASE
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_update(const Shape& s, const UpdateArgs& a, hipStream_t st)
+hipError_t launch_loss(const Shape& s, const LossArgs& a, hipStream_t st)
 {
     const int groups = 256 / s.G;
     const unsigned grid = static_cast<unsigned>((a.B + groups - 1) / groups);
-#define NE_UPDATE_CASE(G_, N_)                                                                   \
+#define NE_CASE(G_, N_)                                                                          \
     if (s.G == G_ && s.NCH == N_) {                                                              \
-        hipLaunchKernelGGL((update_kernel<G_, N_>), dim3(grid), dim3(256), 0, st, a);            \
+        hipLaunchKernelGGL((loss_kernel<G_, N_, 6>), dim3(grid), dim3(256), 0, st, a);           \
         return hipGetLastError();                                                                \
     }
-    NE_UPDATE_CASE(8, 1) NE_UPDATE_CASE(16, 1) NE_UPDATE_CASE(16, 2) NE_UPDATE_CASE(32, 1)
-    NE_UPDATE_CASE(32, 2) NE_UPDATE_CASE(64, 1) NE_UPDATE_CASE(64, 2) NE_UPDATE_CASE(64, 4)
-#undef NE_UPDATE_CASE
+    NE_FOR_EACH_SHAPE(NE_CASE)
+#undef NE_CASE
     return hipErrorInvalidValue;
 }
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
-// Largest grid for one launch: batches beyond this many pairs are rejected.
-constexpr int64_t kMaxBatch = static_cast<int64_t>(1) << 28;
+// Largest batch: keeps every grid and the hash capacity inside 32 bits.
+constexpr int64_t kMaxBatch = static_cast<int64_t>(1) << 22;
+
+bool workspace_layout(int32_t dim, int64_t max_B, int32_t max_K, char* base, Workspace* w)
+{
+    if (dim < 4 || dim > NE_MAX_DIM || dim % 4 != 0 || max_B < 1 || max_B > kMaxBatch || max_K < 0 ||
+        max_K > NE_MAX_NEGATIVES)
+        return false;
+    const uint64_t refs = static_cast<uint64_t>(max_B) * (max_K + 2);
+    uint64_t cap = 1024;
+    while (cap < 2 * refs) cap <<= 1;
+    auto up = [](size_t v) { return (v + 255) & ~static_cast<size_t>(255); };
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char* p = base + off; off = up(off + bytes); return p; };
+    w->cap = static_cast<uint32_t>(cap);
+    w->keys = reinterpret_cast<uint32_t*>(take(cap * 4));
+    w->dupbits = reinterpret_cast<uint32_t*>(take(cap / 32 * 4));
+    w->counters = reinterpret_cast<uint32_t*>(take(16));
+    w->dup_list = reinterpret_cast<uint2*>(take(cap / 4 * sizeof(uint2)));
+    w->ids = reinterpret_cast<int32_t*>(take(refs * 4));
+    w->posbuf = reinterpret_cast<uint32_t*>(take(refs * 4));
+    w->delta = reinterpret_cast<float*>(take(cap * static_cast<size_t>(dim) * 4));
+    w->total_bytes = off;
+    return true;
+}
+
+hipError_t launch_fill(uint32_t* p, size_t n, uint32_t v, hipStream_t st)
+{
+    if (n == 0) return hipSuccess;
+    const size_t want = (n + 255) / 256;
+    const unsigned grid = static_cast<unsigned>(want < 16384 ? want : 16384);
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(grid), dim3(256), 0, st, p, n, v);
+    return hipGetLastError();
+}
 
 ne_status check_batch_args(const ne_tables* t, const ne_alias* al, const int32_t* pairs, int64_t B, int32_t K,
                            Shape* shape)
 {
     if (!t) return fail(NE_ERR_ARG, "tables handle is NULL");
-    if (B < 0 || B > kMaxBatch) return fail(NE_ERR_ARG, "B out of range [0, 2^28]");
-    if (K < 0 || K > NE_MAX_NEGATIVES) return fail(NE_ERR_ARG, "K out of range [0, 63]");
+    if (B < 0 || B > kMaxBatch) return fail(NE_ERR_ARG, "B out of range [0, 2^22]");
+    if (K < 0 || K > NE_MAX_NEGATIVES) return fail(NE_ERR_ARG, "K out of range [0, 62]");
     if (K > 0 && !al) return fail(NE_ERR_ARG, "alias handle is NULL but K > 0");
     if (B > 0 && !pairs) return fail(NE_ERR_ARG, "pairs_dev is NULL");
     if (!aligned(pairs, 8)) return fail(NE_ERR_ARG, "pairs_dev must be 8-byte aligned");
@@ -452,8 +638,17 @@ extern "C" {
 
 const char* ne_last_error(void) { return g_last_error.c_str(); }
 
+size_t ne_workspace_bytes(int32_t dim, int64_t max_batch, int32_t max_negatives)
+{
+    Workspace w;
+    if (!workspace_layout(dim, max_batch, max_negatives, nullptr, &w)) return 0;
+    return w.total_bytes;
+}
+
 ne_status ne_create_tables(ne_tables** out, int64_t num_nodes, int32_t dim, float* vertex_dev,
-                           float* context_dev, uint64_t seed, int32_t init, void* hip_stream)
+                           float* context_dev, uint64_t seed, int32_t init, int64_t max_batch,
+                           int32_t max_negatives, void* workspace_dev, size_t workspace_bytes,
+                           void* hip_stream)
 {
     if (!out) return fail(NE_ERR_ARG, "out is NULL");
     *out = nullptr;
@@ -464,10 +659,33 @@ ne_status ne_create_tables(ne_tables** out, int64_t num_nodes, int32_t dim, floa
     if (!vertex_dev || !context_dev) return fail(NE_ERR_ARG, "table pointer is NULL");
     if (!aligned(vertex_dev, 16) || !aligned(context_dev, 16))
         return fail(NE_ERR_ARG, "table pointers must be 16-byte aligned");
-    ne_tables* t = new (std::nothrow) ne_tables{num_nodes, dim, vertex_dev, context_dev, seed};
+    ne_tables* t = new (std::nothrow) ne_tables{};
     if (!t) return fail(NE_ERR_NOMEM, "host allocation failed");
+    t->num_nodes = num_nodes; t->dim = dim; t->vertex = vertex_dev; t->context = context_dev; t->seed = seed;
+    t->max_batch = 0; t->max_negatives = 0; t->batches_done = 0; t->profile_every = 0; t->ev_used = 0;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+
+    if (workspace_dev || max_batch > 0) {   // training requested
+        Workspace w;
+        if (!workspace_layout(dim, max_batch, max_negatives, static_cast<char*>(workspace_dev), &w)) {
+            delete t;
+            return fail(NE_ERR_ARG, "max_batch must be in [1, 2^22] and max_negatives in [0, 62]");
+        }
+        if (!workspace_dev || !aligned(workspace_dev, 256) || workspace_bytes < w.total_bytes) {
+            delete t;
+            return fail(NE_ERR_ARG, "workspace_dev is NULL, not 256-byte aligned, or smaller than ne_workspace_bytes()");
+        }
+        t->ws = w; t->max_batch = max_batch; t->max_negatives = max_negatives;
+        hipError_t e = launch_fill(w.keys, w.cap, kEmptyKey, st);
+        if (e == hipSuccess) e = launch_fill(w.dupbits, w.cap / 32, 0u, st);
+        if (e == hipSuccess) e = launch_fill(w.counters, 4, 0u, st);
+        if (e == hipSuccess) e = launch_fill(reinterpret_cast<uint32_t*>(w.delta), static_cast<size_t>(w.cap) * dim, 0u, st);
+        if (e != hipSuccess) {
+            delete t;
+            return fail(NE_ERR_HIP, std::string("workspace init launch: ") + hipGetErrorString(e));
+        }
+    }
     if (init) {
-        hipStream_t st = static_cast<hipStream_t>(hip_stream);
         const int64_t total = num_nodes * (dim / 4);
         const int64_t want = (total + 255) / 256;
         const unsigned grid = static_cast<unsigned>(want < 65536 * 4 ? (want > 0 ? want : 1) : 65536 * 4);
@@ -484,7 +702,49 @@ ne_status ne_create_tables(ne_tables** out, int64_t num_nodes, int32_t dim, floa
     return NE_OK;
 }
 
-void ne_destroy_tables(ne_tables* t) { delete t; }
+void ne_destroy_tables(ne_tables* t)
+{
+    if (!t) return;
+    for (hipEvent_t e : t->ev_start) (void)hipEventDestroy(e);
+    for (hipEvent_t e : t->ev_stop) (void)hipEventDestroy(e);
+    delete t;
+}
+
+ne_status ne_profile_enable(ne_tables* t, int32_t every_n, int32_t max_samples)
+{
+    if (!t) return fail(NE_ERR_ARG, "tables handle is NULL");
+    if (every_n < 0 || max_samples < 0 || max_samples > 65536) return fail(NE_ERR_ARG, "every_n or max_samples out of range");
+    t->profile_every = every_n;
+    t->ev_used = 0;
+    while (every_n > 0 && t->ev_start.size() < static_cast<size_t>(max_samples)) {
+        hipEvent_t a = nullptr, b = nullptr;
+        NE_HIP_CHECK(hipEventCreate(&a));
+        hipError_t e = hipEventCreate(&b);
+        if (e != hipSuccess) {
+            (void)hipEventDestroy(a);
+            return fail(NE_ERR_HIP, std::string("hipEventCreate: ") + hipGetErrorString(e));
+        }
+        t->ev_start.push_back(a);
+        t->ev_stop.push_back(b);
+    }
+    return NE_OK;
+}
+
+ne_status ne_profile_read(ne_tables* t, double* total_ms_host, int64_t* samples_host)
+{
+    if (!t || !total_ms_host || !samples_host) return fail(NE_ERR_ARG, "NULL argument");
+    double total = 0.0;
+    for (size_t i = 0; i < t->ev_used; ++i) {
+        NE_HIP_CHECK(hipEventSynchronize(t->ev_stop[i]));
+        float ms = 0.0f;
+        NE_HIP_CHECK(hipEventElapsedTime(&ms, t->ev_start[i], t->ev_stop[i]));
+        total += static_cast<double>(ms);
+    }
+    *total_ms_host = total;
+    *samples_host = static_cast<int64_t>(t->ev_used);
+    t->ev_used = 0;
+    return NE_OK;
+}
 void ne_destroy_alias(ne_alias* a) { delete a; }
 
 ne_status ne_build_neg_alias(ne_alias** out, const uint32_t* degree_host, int64_t n, int32_t base,
@@ -551,48 +811,57 @@ ne_status ne_build_neg_alias(ne_alias** out, const uint32_t* degree_host, int64_
     return NE_OK;
 }
 
-size_t ne_staging_bytes(int64_t B, int32_t dim, int32_t K)
-{
-    if (B < 0 || B > kMaxBatch || dim < 4 || dim > NE_MAX_DIM || dim % 4 != 0 || K < 0 || K > NE_MAX_NEGATIVES)
-        return 0;
-    return staging_layout(B > 0 ? B : 1, dim, K).total;
-}
-
 ne_status ne_train_batch(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t B, int32_t K,
-                         float lr, uint64_t sample_base, void* staging_dev, size_t staging_bytes,
-                         int32_t* neg_out_dev, void* hip_stream)
+                         float lr, uint64_t sample_base, int32_t* neg_out_dev, void* hip_stream)
 {
     Shape shape;
     ne_status rc = check_batch_args(t, al, pairs_dev, B, K, &shape);
     if (rc != NE_OK) return rc;
     if (!std::isfinite(lr)) return fail(NE_ERR_ARG, "lr is not finite");
+    if (t->max_batch <= 0) return fail(NE_ERR_STATE, "tables were created without a training workspace");
+    if (B > t->max_batch || K > t->max_negatives)
+        return fail(NE_ERR_ARG, "B or K exceeds the max_batch / max_negatives the workspace was sized for");
     if (B == 0) return NE_OK;
-    const StagingLayout L = staging_layout(B, t->dim, K);
-    if (!staging_dev || !aligned(staging_dev, 16)) return fail(NE_ERR_ARG, "staging_dev is NULL or not 16-byte aligned");
-    if (staging_bytes < L.total) return fail(NE_ERR_ARG, "staging buffer smaller than ne_staging_bytes(B, dim, K)");
 
-    char* sp = static_cast<char*>(staging_dev);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    ScoreArgs sa{};
-    sa.X = reinterpret_cast<const float4*>(t->vertex);
-    sa.C = reinterpret_cast<const float4*>(t->context);
-    sa.pairs = reinterpret_cast<const int2*>(pairs_dev);
-    sa.B = B; sa.K = K; sa.d4 = t->dim / 4; sa.lr = lr; sa.sample_base = sample_base;
-    sa.k0 = static_cast<uint32_t>(t->seed); sa.k1 = static_cast<uint32_t>(t->seed >> 32);
-    sa.alias = al ? al->table : nullptr; sa.alias_n = al ? static_cast<uint64_t>(al->n) : 1; sa.alias_base = al ? al->base : 0;
-    sa.gbuf = reinterpret_cast<float*>(sp + L.g_off);
-    sa.nbuf = reinterpret_cast<int32_t*>(sp + L.n_off);
-    sa.xbuf = reinterpret_cast<float4*>(sp + L.x_off);
-    sa.dxbuf = reinterpret_cast<float4*>(sp + L.dx_off);
-    sa.neg_out = neg_out_dev; sa.loss = nullptr;
-    hipError_t e = launch_score<true>(shape, sa, st);
-    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("score launch: ") + hipGetErrorString(e));
+    const Workspace& w = t->ws;
+    const unsigned parity = static_cast<unsigned>(t->batches_done & 1);
 
-    UpdateArgs ua{};
-    ua.X = t->vertex; ua.C = t->context; ua.pairs = sa.pairs; ua.B = B; ua.K = K; ua.d4 = sa.d4;
-    ua.gbuf = sa.gbuf; ua.nbuf = sa.nbuf; ua.xbuf = sa.xbuf; ua.dxbuf = sa.dxbuf;
-    e = launch_update(shape, ua, st);
-    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("update launch: ") + hipGetErrorString(e));
+    PrepArgs pa{};
+    pa.pairs = reinterpret_cast<const int2*>(pairs_dev);
+    pa.B = B; pa.K = K; pa.sample_base = sample_base;
+    pa.k0 = static_cast<uint32_t>(t->seed); pa.k1 = static_cast<uint32_t>(t->seed >> 32);
+    pa.alias = al ? al->table : nullptr; pa.alias_n = al ? static_cast<uint64_t>(al->n) : 1; pa.alias_base = al ? al->base : 0;
+    pa.keys = w.keys; pa.mask = w.cap - 1; pa.dupbits = w.dupbits; pa.n_dup = w.counters + parity;
+    pa.dup_list = w.dup_list; pa.ids = w.ids; pa.posbuf = w.posbuf; pa.neg_out = neg_out_dev;
+    const int64_t refs = B * (K + 2);
+    hipLaunchKernelGGL(prep_kernel, dim3(static_cast<unsigned>((refs + 255) / 256)), dim3(256), 0, st, pa);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("prep launch: ") + hipGetErrorString(e));
+
+    TrainArgs ta{};
+    ta.X = reinterpret_cast<float4*>(t->vertex); ta.C = reinterpret_cast<float4*>(t->context);
+    ta.B = B; ta.K = K; ta.d4 = t->dim / 4; ta.lr = lr;
+    ta.ids = w.ids; ta.posbuf = w.posbuf; ta.dupbits = w.dupbits; ta.delta = w.delta;
+    const bool timed = t->profile_every > 0 && t->batches_done % static_cast<uint64_t>(t->profile_every) == 0 &&
+                       t->ev_used < t->ev_start.size();
+    if (timed) NE_HIP_CHECK(hipEventRecord(t->ev_start[t->ev_used], st));
+    e = launch_train(shape, ta, st);
+    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("train launch: ") + hipGetErrorString(e));
+    if (timed) {
+        NE_HIP_CHECK(hipEventRecord(t->ev_stop[t->ev_used], st));
+        t->ev_used += 1;
+    }
+
+    ApplyArgs aa{};
+    aa.X = ta.X; aa.C = ta.C; aa.d4 = ta.d4; aa.delta = reinterpret_cast<float4*>(w.delta);
+    aa.dup_list = w.dup_list; aa.n_dup = w.counters + parity; aa.n_dup_next = w.counters + (parity ^ 1);
+    aa.keys = w.keys; aa.dupbits = w.dupbits; aa.cap = w.cap;
+    const unsigned apply_grid = static_cast<unsigned>(w.cap / 256 < 2048 ? w.cap / 256 : 2048);
+    hipLaunchKernelGGL(apply_kernel, dim3(apply_grid), dim3(256), 0, st, aa);
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("apply launch: ") + hipGetErrorString(e));
+    t->batches_done += 1;
     return NE_OK;
 }
 
@@ -604,16 +873,16 @@ ne_status ne_eval_loss(const ne_tables* t, const ne_alias* al, const int32_t* pa
     if (rc != NE_OK) return rc;
     if (!loss_sum_dev || !aligned(loss_sum_dev, 8)) return fail(NE_ERR_ARG, "loss_sum_dev is NULL or misaligned");
     if (B == 0) return NE_OK;
-    ScoreArgs sa{};
-    sa.X = reinterpret_cast<const float4*>(t->vertex);
-    sa.C = reinterpret_cast<const float4*>(t->context);
-    sa.pairs = reinterpret_cast<const int2*>(pairs_dev);
-    sa.B = B; sa.K = K; sa.d4 = t->dim / 4; sa.lr = 0.0f; sa.sample_base = sample_base;
-    sa.k0 = static_cast<uint32_t>(t->seed); sa.k1 = static_cast<uint32_t>(t->seed >> 32);
-    sa.alias = al ? al->table : nullptr; sa.alias_n = al ? static_cast<uint64_t>(al->n) : 1; sa.alias_base = al ? al->base : 0;
-    sa.neg_out = neg_out_dev; sa.loss = loss_sum_dev;
-    hipError_t e = launch_score<false>(shape, sa, static_cast<hipStream_t>(hip_stream));
-    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("eval launch: ") + hipGetErrorString(e));
+    LossArgs la{};
+    la.X = reinterpret_cast<const float4*>(t->vertex);
+    la.C = reinterpret_cast<const float4*>(t->context);
+    la.pairs = reinterpret_cast<const int2*>(pairs_dev);
+    la.B = B; la.K = K; la.d4 = t->dim / 4; la.sample_base = sample_base;
+    la.k0 = static_cast<uint32_t>(t->seed); la.k1 = static_cast<uint32_t>(t->seed >> 32);
+    la.alias = al ? al->table : nullptr; la.alias_n = al ? static_cast<uint64_t>(al->n) : 1; la.alias_base = al ? al->base : 0;
+    la.neg_out = neg_out_dev; la.loss = loss_sum_dev;
+    hipError_t e = launch_loss(shape, la, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("loss launch: ") + hipGetErrorString(e));
     return NE_OK;
 }
 
@@ -621,7 +890,7 @@ ne_status ne_validate_pairs(const ne_tables* t, const int32_t* pairs_dev, int64_
                             unsigned long long* bad_count_dev, void* hip_stream)
 {
     if (!t || !bad_count_dev) return fail(NE_ERR_ARG, "NULL argument");
-    if (B < 0 || B > kMaxBatch * 16) return fail(NE_ERR_ARG, "B out of range");
+    if (B < 0 || B > (static_cast<int64_t>(1) << 40)) return fail(NE_ERR_ARG, "B out of range");
     if (B == 0) return NE_OK;
     if (!pairs_dev) return fail(NE_ERR_ARG, "pairs_dev is NULL");
     const int64_t count = 2 * B;

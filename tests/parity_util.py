@@ -36,19 +36,20 @@ class GpuModel:
             self.vertex.copy_(torch.from_numpy(X))
             self.context.copy_(torch.from_numpy(C))
             init = False
-        self.tables = ne.ne_create_tables(self.vertex, self.context, seed, init=init)
+        self.workspace = torch.empty(ne.ne_workspace_bytes(d, max(max_B, 1), K), dtype=torch.uint8, device=dev)
+        self.tables = ne.ne_create_tables(self.vertex, self.context, seed, init=init, max_batch=max(max_B, 1),
+                                          max_negatives=K, workspace=self.workspace)
         self.alias = None
         if degree is not None:
             n = len(degree)
             self.alias_table = torch.empty((n, 2), dtype=torch.int32, device=dev)
             self.alias = ne.ne_build_neg_alias(np.asarray(degree, dtype=np.uint32), base, self.alias_table)
-        self.staging = torch.empty(max(ne.ne_staging_bytes(max_B, d, K), 16), dtype=torch.uint8, device=dev)
         self.neg_out = torch.empty((max(max_B, 1), max(K, 1)), dtype=torch.int32, device=dev)
         self.loss = torch.zeros((), dtype=torch.float64, device=dev)
 
     def train(self, pairs_dev, lr, sample_base, want_neg=True):
         B = pairs_dev.shape[0]
-        ne.ne_train_batch(self.tables, self.alias, pairs_dev, self.K, lr, sample_base, self.staging,
+        ne.ne_train_batch(self.tables, self.alias, pairs_dev, self.K, lr, sample_base,
                           self.neg_out if want_neg else None)
         if want_neg:
             return self.neg_out[:B, :self.K].cpu().numpy() if self.K > 0 else np.zeros((B, 0), np.int32)

@@ -36,28 +36,35 @@ def test_host_side_argument_errors():
     L = ne.lib()
     out = ctypes.c_void_p()
     fake = ctypes.c_void_p(0x1000)      # never dereferenced: every call below fails on the host first
-    assert L.ne_create_tables(None, 10, 8, fake, fake, 0, 0, None) == ne.NE_ERR_ARG
-    assert L.ne_create_tables(ctypes.byref(out), 0, 8, fake, fake, 0, 0, None) == ne.NE_ERR_ARG
-    assert L.ne_create_tables(ctypes.byref(out), 10, 6, fake, fake, 0, 0, None) == ne.NE_ERR_ARG
-    assert L.ne_create_tables(ctypes.byref(out), 10, 2048, fake, fake, 0, 0, None) == ne.NE_ERR_ARG
-    assert L.ne_create_tables(ctypes.byref(out), 2**31, 8, fake, fake, 0, 0, None) == ne.NE_ERR_ARG
-    assert L.ne_create_tables(ctypes.byref(out), 10, 8, None, fake, 0, 0, None) == ne.NE_ERR_ARG
-    assert L.ne_create_tables(ctypes.byref(out), 10, 8, ctypes.c_void_p(0x1004), fake, 0, 0, None) == ne.NE_ERR_ARG
+
+    def create(nodes=10, dim=8, v=fake, c=fake, max_b=0, max_k=0, ws=None, ws_bytes=0, outp=ctypes.byref(out)):
+        return L.ne_create_tables(outp, nodes, dim, v, c, 0, 0, max_b, max_k, ws, ws_bytes, None)
+
+    assert create(outp=None) == ne.NE_ERR_ARG
+    assert create(nodes=0) == ne.NE_ERR_ARG
+    assert create(dim=6) == ne.NE_ERR_ARG
+    assert create(dim=2048) == ne.NE_ERR_ARG
+    assert create(nodes=2**31) == ne.NE_ERR_ARG
+    assert create(v=None) == ne.NE_ERR_ARG
+    assert create(v=ctypes.c_void_p(0x1004)) == ne.NE_ERR_ARG
     assert b"aligned" in L.ne_last_error()
-    # bind-only (init = 0) enqueues nothing, so it works without a GPU
-    assert L.ne_create_tables(ctypes.byref(out), 10, 8, fake, fake, 7, 0, None) == ne.NE_OK
+    assert create(max_b=16, max_k=5, ws=None) == ne.NE_ERR_ARG           # training without workspace
+    assert create(max_b=16, max_k=5, ws=fake, ws_bytes=64) == ne.NE_ERR_ARG   # workspace too small
+    assert b"workspace" in L.ne_last_error()
+    assert create(max_b=16, max_k=63, ws=fake, ws_bytes=1 << 30) == ne.NE_ERR_ARG
+    # bind-only (init = 0, no workspace) enqueues nothing, so it works without a GPU
+    assert create() == ne.NE_OK
     tables = out.value
-    assert L.ne_train_batch(None, None, fake, 1, 0, 0.1, 0, fake, 1 << 20, None, None) == ne.NE_ERR_ARG
-    assert L.ne_train_batch(tables, None, fake, -1, 0, 0.1, 0, fake, 1 << 20, None, None) == ne.NE_ERR_ARG
-    assert L.ne_train_batch(tables, None, fake, 1, 64, 0.1, 0, fake, 1 << 20, None, None) == ne.NE_ERR_ARG
-    assert L.ne_train_batch(tables, None, fake, 1, 5, 0.1, 0, fake, 1 << 20, None, None) == ne.NE_ERR_ARG
-    assert L.ne_train_batch(tables, None, None, 1, 0, 0.1, 0, fake, 1 << 20, None, None) == ne.NE_ERR_ARG
-    assert L.ne_train_batch(tables, None, fake, 1, 0, float("nan"), 0, fake, 1 << 20, None, None) == ne.NE_ERR_ARG
-    assert L.ne_train_batch(tables, None, fake, 1, 0, 0.1, 0, fake, 8, None, None) == ne.NE_ERR_ARG
-    assert b"staging" in L.ne_last_error()
-    assert L.ne_train_batch(tables, None, fake, 0, 0, 0.1, 0, None, 0, None, None) == ne.NE_OK   # B = 0
+    assert L.ne_train_batch(None, None, fake, 1, 0, 0.1, 0, None, None) == ne.NE_ERR_ARG
+    assert L.ne_train_batch(tables, None, fake, -1, 0, 0.1, 0, None, None) == ne.NE_ERR_ARG
+    assert L.ne_train_batch(tables, None, fake, 1, 63, 0.1, 0, None, None) == ne.NE_ERR_ARG
+    assert L.ne_train_batch(tables, None, fake, 1, 5, 0.1, 0, None, None) == ne.NE_ERR_ARG      # K > 0, no alias
+    assert L.ne_train_batch(tables, None, None, 1, 0, 0.1, 0, None, None) == ne.NE_ERR_ARG
+    assert L.ne_train_batch(tables, None, fake, 1, 0, float("nan"), 0, None, None) == ne.NE_ERR_ARG
+    assert L.ne_train_batch(tables, None, fake, 1, 0, 0.1, 0, None, None) == ne.NE_ERR_STATE    # no workspace
+    assert b"workspace" in L.ne_last_error()
     assert L.ne_eval_loss(tables, None, fake, 1, 0, 0, None, None, None) == ne.NE_ERR_ARG
-    assert L.ne_eval_loss(tables, None, fake, 0, 0, 0, fake, None, None) == ne.NE_OK
+    assert L.ne_eval_loss(tables, None, fake, 0, 0, 0, fake, None, None) == ne.NE_OK            # B = 0
     assert L.ne_build_neg_alias(ctypes.byref(out), None, 4, 0, fake, None) == ne.NE_ERR_ARG
     deg = (ctypes.c_uint32 * 4)(0, 0, 0, 0)
     assert L.ne_build_neg_alias(ctypes.byref(out), deg, 4, 0, fake, None) == ne.NE_ERR_ARG
@@ -67,9 +74,12 @@ def test_host_side_argument_errors():
     L.ne_destroy_tables(tables)
 
 
-def test_staging_bytes():
-    assert ne.ne_staging_bytes(4096, 128, 5) >= 4096 * (2 * 128 * 4 + 6 * 4 + 5 * 4)
-    assert ne.ne_staging_bytes(4096, 130, 5) == 0
-    assert ne.ne_staging_bytes(-1, 128, 5) == 0
-    assert ne.ne_staging_bytes(10, 128, 64) == 0
-    assert ne.ne_staging_bytes(0, 128, 5) > 0
+def test_workspace_bytes():
+    w = ne.ne_workspace_bytes(128, 4096, 5)
+    refs = 4096 * 7
+    assert w >= 2 * refs * 128 * 4 + 2 * refs * 4
+    assert ne.ne_workspace_bytes(130, 4096, 5) == 0
+    assert ne.ne_workspace_bytes(128, 0, 5) == 0
+    assert ne.ne_workspace_bytes(128, 10, 63) == 0
+    assert ne.ne_workspace_bytes(128, ne.NE_MAX_BATCH + 1, 5) == 0
+    assert ne.ne_workspace_bytes(128, 8192, 5) > w
