@@ -88,6 +88,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="c3", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-pipeline", action="store_true", help="one stream, ne_train_batch per step")
     ap.add_argument("--cpu-batches", type=int, default=0, help="oracle batches to time (0 = auto)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -125,17 +126,37 @@ def main():
     lrs = [np.float32(wl.linear_decay_lr(0.025, i * B, total_pairs)) for i in range(n_batches)]
     pairs = bp.pairs
 
-    def step(i):
-        s, n, _, j = sched[i]
-        ne.ne_train_batch(tables, aliases[j], pairs[s:s + n], K, float(lrs[i]), i * B)
+    s_prep, s_train = torch.cuda.Stream(), torch.cuda.Stream()
 
-    for i in range(args.warmup):
-        step(i)
+    def run(first, last):
+        """Batches [first, last): the id-only half of batch i+1 (negative sampling, shared-row
+        detection) runs on s_prep while batch i trains on s_train; two preparation slots."""
+        if args.no_pipeline:
+            for i in range(first, last):
+                s, n, _, j = sched[i]
+                ne.ne_train_batch(tables, aliases[j], pairs[s:s + n], K, float(lrs[i]), i * B, stream=s_train)
+            return
+        prepared = [torch.cuda.Event() for _ in range(2)]
+        trained = [torch.cuda.Event() for _ in range(2)]
+        for i in range(first, last + 1):
+            if i < last:
+                if i - 2 >= first:
+                    s_prep.wait_event(trained[i & 1])          # slot i&1 was released by batch i-2
+                s, n, _, j = sched[i]
+                ne.ne_prepare_batch(tables, aliases[j], pairs[s:s + n], K, i * B, i & 1, stream=s_prep)
+                prepared[i & 1].record(s_prep)
+            if i - 1 >= first:
+                u = i - 1
+                s_train.wait_event(prepared[u & 1])
+                ne.ne_train_prepared(tables, u & 1, float(lrs[u]), stream=s_train)
+                trained[u & 1].record(s_train)
+
+    torch.cuda.synchronize()
+    run(0, args.warmup)
     torch.cuda.synchronize()
     ne.ne_profile_enable(tables, 4, args.steps // 4 + 2)
     t_start = time.perf_counter()
-    for i in range(args.warmup, n_batches):
-        step(i)
+    run(args.warmup, n_batches)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
     kern_ms, kern_n = ne.ne_profile_read(tables)
@@ -159,6 +180,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": name, "nodes": V, "dim": d, "negatives": K, "batch": B, "block_grid": f"{grid}x{grid}",
+                   "streams": 1 if args.no_pipeline else 2,
                    "end_to_end_GBps": pairs_per_s * bpp / 1e9},
         "roofline": {"bound": "hbm", "kernel": "train_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": (achieved / HBM_PEAK_GBS) if achieved else None,

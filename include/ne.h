@@ -109,6 +109,27 @@ ne_status ne_train_batch(ne_tables* tables, const ne_alias* alias, const int32_t
                          void* hip_stream);
 
 /*
+ * The same step in two halves, for callers that overlap the id-only half of batch t+1 with the
+ * table-touching half of batch t on two streams.
+ *
+ * ne_prepare_batch draws the negatives of the batch and finds out which table rows more than one
+ * of its (src, ctx, negative) references name (Algorithm 1: EdgeSample and NegativeSample).  It reads
+ * pairs_dev and the alias table, writes only the handle's workspace (preparation slot `slot`, 0 or 1)
+ * and neg_out_dev, and never touches the embedding tables.  Arguments as for ne_train_batch.
+ *
+ * ne_train_prepared scores the prepared batch and applies its update (Algorithm 1: the Train calls),
+ * then releases the slot.  It must be ordered after the ne_prepare_batch of the same slot (same
+ * stream, or an event the caller records and waits on), and after every earlier ne_train_prepared on
+ * the same handle.  A slot can hold one batch: prepare - train - prepare - ...; the next
+ * ne_prepare_batch of a slot must be ordered after the ne_train_prepared that used it.
+ * Errors: NE_ERR_ARG, NE_ERR_STATE (slot busy / nothing prepared), NE_ERR_HIP.
+ */
+ne_status ne_prepare_batch(ne_tables* tables, const ne_alias* alias, const int32_t* pairs_dev, int64_t B,
+                           int32_t K, uint64_t sample_base, int32_t* neg_out_dev, int32_t slot,
+                           void* hip_stream);
+ne_status ne_train_prepared(ne_tables* tables, int32_t slot, float lr, void* hip_stream);
+
+/*
  * Loss of a batch at the current tables with the same negatives ne_train_batch would draw; nothing
  * is updated.  Adds  sum_b [ -log sigmoid(s_b0) - sum_k log sigmoid(-s_bk) ]  (fp32 terms, fp64 sum)
  * to *loss_sum_dev.

@@ -1,23 +1,29 @@
 // SGNS node-embedding training for MI355X (gfx950): HIP kernels and the C ABI declared in ne.h.
 //
-// One batch of the embedding-training loop (Algorithm 1; Sec. II-A "Training Process") is three
-// kernels on the caller's stream:
+// One batch of the embedding-training loop (Algorithm 1; Sec. II-A "Training Process") is four
+// kernels:
 //
-//   prep   (ids only)  one thread per row reference (src, ctx, K negatives of every pair): draws the
-//          negative (Philox + alias table), inserts (table, row) into a batch-local hash set and
-//          learns whether another reference of the batch names the same row.  Rows named at least
-//          twice are "shared"; each gets the hash position as its delta slot.
-//   train  one lane group per pair: gathers x = vertex[src] and the K+1 context rows (dwordx4),
-//          reduces the K+1 dot products with DPP, forms g_j and the deltas.  A row that only this
-//          pair names is rewritten in place from registers (old + delta, one plain store: every row
-//          costs one read and one write).  A shared row is left untouched - other pairs must still
-//          read its pre-batch value - and its delta is added to the row's slot with fp32 atomics.
-//   apply  adds each slot to its table row, zeroes the slot and empties the hash set.
+//   claim, resolve (ids only; ne_prepare_batch)  one thread per row reference (src, ctx and the K
+//          negatives of every pair).  claim draws the negative (Philox + alias table) and stores
+//          (key, reference index) at the key's hash position with a plain 8-byte store; whichever
+//          store lands last owns the position.  resolve reads the position back: a reference whose
+//          key owns it but whose index differs has found a second reference of the same row and
+//          flags the row as shared; references whose key lost the position (a different row hashed
+//          there) fall back to compare-and-swap probing.  Returning atomics retire slowly on this
+//          chip, so only that minority uses them.
+//   train  (ne_train_prepared) one lane group per pair: gathers x = vertex[src] and the K+1 context
+//          rows (dwordx4), reduces the K+1 dot products with DPP, forms g_j and the deltas.  A row
+//          that only this pair names is rewritten in place from registers (old + delta, one plain
+//          store: the row costs one read and one write).  A shared row is left untouched - other
+//          pairs must still read its pre-batch value - and its delta is added to the row's slot
+//          (indexed by hash position) with fp32 atomics.
+//   apply  adds each shared row's slot to the table row, zeroes the slot and empties the hash table.
 //
 // This is exactly minibatch-synchronous: no row that a second reference could read is written
 // before the apply kernel, and all contributions to a row are summed.  fp32 atomics on gfx950
 // retire one dword per L2 channel clock, far below the rate of plain row stores, which is why only
-// shared rows go through them.
+// shared rows go through them.  The id-only kernels of batch t+1 do not touch the tables, so a
+// caller may run them on a second stream while batch t trains (two preparation slots).
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -52,15 +58,17 @@ static ne_status fail(ne_status st, const std::string& msg)
 namespace {
 
 // Device workspace of a tables handle (caller's memory, carved up here).
+struct PrepSlot {
+    unsigned long long* slots;  // [cap]  (key << 32 | reference index) per hash position; ~0 = empty
+    uint8_t* shared;            // [cap]  1 <=> the row whose key sits at this position is shared
+    int32_t* ids;               // [max_B][max_K+2]  src, ctx, negatives
+    uint32_t* posbuf;           // [max_B][max_K+2]  final hash position; bit 31: this reference
+                                //                   cleans up (and applies) the position
+};
 struct Workspace {
-    uint32_t* keys;      // [cap]     hash set of (table bit << 31 | row); 0xFFFFFFFF = empty
-    uint32_t* dupbits;   // [cap/32]  bit pos set <=> the row at keys[pos] is shared
-    uint32_t* counters;  // [4]       [0],[1]: number of shared rows of the even / odd batch
-    uint2* dup_list;     // [cap/4]   (pos, key) of every shared row of the batch
-    int32_t* ids;        // [max_B][max_K+2]  src, ctx, negatives
-    uint32_t* posbuf;    // [max_B][max_K+2]  hash position of each reference
-    float* delta;        // [cap][dim]        per-slot fp32 accumulators, zero between batches
-    uint32_t cap;        // power of two >= 2 * max_B * (max_K + 2)
+    PrepSlot prep[2];
+    float* delta;        // [cap][dim]  per-position fp32 accumulators, zero between batches
+    uint32_t cap;        // power of two >= 4 * max_B * (max_K + 2)
     size_t total_bytes;
 };
 
@@ -75,7 +83,8 @@ struct ne_tables {
     int64_t max_batch;
     int32_t max_negatives;
     Workspace ws;
-    uint64_t batches_done;   // parity selects the shared-row counter
+    uint64_t batches_done;
+    struct { int64_t B; int32_t K; bool ready; } prepared[2];
     // optional timing of the train kernel with HIP events (ne_profile_enable / ne_profile_read)
     int32_t profile_every;
     std::vector<hipEvent_t> ev_start, ev_stop;
@@ -94,7 +103,6 @@ struct ne_alias {
 namespace {
 
 enum : uint32_t { kStreamNegative = 0, kStreamInit = 1, kStreamSharedNegative = 2 };
-constexpr uint32_t kEmptyKey = 0xFFFFFFFFu;
 
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11).
 __device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint32_t k0, uint32_t k1)
@@ -198,9 +206,15 @@ __global__ __launch_bounds__(256) void init_tables_kernel(float4* __restrict__ X
 }
 
 // ---------------------------------------------------------------------------------------------
-// prep kernel: one thread per row reference.  Reference j of pair b: j = 0 the source row (vertex
-// table), j = 1 the positive context row, j = 2.. negative j-2 (context table).
+// claim + resolve kernels: one thread per row reference.  Reference j of pair b: j = 0 the source
+// row (vertex table), j = 1 the positive context row, j = 2.. negative j-2 (context table).
+// key = row | (context table ? 1 << 31 : 0).
 // ---------------------------------------------------------------------------------------------
+constexpr unsigned long long kEmptySlot = ~0ull;
+constexpr uint32_t kPosMask = 0x7FFFFFFFu;
+
+__device__ __forceinline__ uint32_t hash_key(uint32_t key, uint32_t mask) { return ((key * 0x9E3779B1u) >> 7) & mask; }
+
 struct PrepArgs {
     const int2* pairs;
     int64_t B;
@@ -210,17 +224,15 @@ struct PrepArgs {
     const uint2* alias;
     uint64_t alias_n;
     int32_t alias_base;
-    uint32_t* keys;
+    unsigned long long* slots;
     uint32_t mask;        // cap - 1
-    uint32_t* dupbits;
-    uint32_t* n_dup;
-    uint2* dup_list;
+    uint8_t* shared;
     int32_t* ids;
     uint32_t* posbuf;
     int32_t* neg_out;
 };
 
-__global__ __launch_bounds__(256) void prep_kernel(PrepArgs a)
+__global__ __launch_bounds__(256) void claim_kernel(PrepArgs a)
 {
     const int R = a.K + 2;
     const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
@@ -236,26 +248,39 @@ __global__ __launch_bounds__(256) void prep_kernel(PrepArgs a)
                            a.alias_n, a.alias_base);
         if (a.neg_out) a.neg_out[b * a.K + (j - 2)] = id;
     }
-    const uint32_t key = static_cast<uint32_t>(id) | (j == 0 ? 0u : 0x80000000u);
-    uint32_t pos = (key * 0x9E3779B1u) >> 7 & a.mask;
-    bool existed;
-    // the set holds at most cap/2 keys, so an empty position is always reached
-    while (true) {
-        const uint32_t prev = atomicCAS(&a.keys[pos], kEmptyKey, key);
-        if (prev == kEmptyKey) { existed = false; break; }
-        if (prev == key) { existed = true; break; }
-        pos = (pos + 1) & a.mask;
-    }
     a.ids[t] = id;
-    a.posbuf[t] = pos;
-    if (existed) {
-        const uint32_t bit = 1u << (pos & 31);
-        const uint32_t old = atomicOr(&a.dupbits[pos >> 5], bit);
-        if (!(old & bit)) {
-            const uint32_t slot = atomicAdd(a.n_dup, 1u);
-            a.dup_list[slot] = make_uint2(pos, key);
+    const uint32_t key = static_cast<uint32_t>(id) | (j == 0 ? 0u : 0x80000000u);
+    a.slots[hash_key(key, a.mask)] = (static_cast<unsigned long long>(key) << 32) | static_cast<uint32_t>(t);
+}
+
+__global__ __launch_bounds__(256) void resolve_kernel(PrepArgs a)
+{
+    const int R = a.K + 2;
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (t >= a.B * R) return;
+    const int j = static_cast<int>(t % R);
+    const uint32_t key = static_cast<uint32_t>(a.ids[t]) | (j == 0 ? 0u : 0x80000000u);
+    uint32_t pos = hash_key(key, a.mask);
+    const unsigned long long owner = a.slots[pos];
+    if (static_cast<uint32_t>(owner >> 32) == key) {
+        // my row owns its home position; the reference whose store landed last cleans up
+        if (static_cast<uint32_t>(owner) == static_cast<uint32_t>(t)) {
+            pos |= 0x80000000u;
+        } else {
+            a.shared[pos] = 1;
+        }
+    } else {
+        // another row owns the home position: probe onwards.  Positions only ever go from empty to
+        // occupied here, and the table holds at most cap/4 keys, so the walk ends.
+        const unsigned long long mine = (static_cast<unsigned long long>(key) << 32) | static_cast<uint32_t>(t);
+        while (true) {
+            pos = (pos + 1) & a.mask;
+            const unsigned long long prev = atomicCAS(&a.slots[pos], kEmptySlot, mine);
+            if (prev == kEmptySlot) { pos |= 0x80000000u; break; }
+            if (static_cast<uint32_t>(prev >> 32) == key) { a.shared[pos] = 1; break; }
         }
     }
+    a.posbuf[t] = pos;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -271,7 +296,7 @@ struct TrainArgs {
     float lr;
     const int32_t* ids;
     const uint32_t* posbuf;
-    const uint32_t* dupbits;
+    const uint8_t* shared;
     float* delta;
 };
 
@@ -308,8 +333,8 @@ __global__ __launch_bounds__(256) void train_kernel(TrainArgs a)
     int shared_mine = 0;
     if (lg < R) {
         id_mine = a.ids[b * R + lg];
-        pos_mine = a.posbuf[b * R + lg];
-        shared_mine = (a.dupbits[pos_mine >> 5] >> (pos_mine & 31)) & 1;
+        pos_mine = a.posbuf[b * R + lg] & kPosMask;
+        shared_mine = a.shared[pos_mine];
     }
 
     const int32_t src = __shfl(id_mine, 0, G);
@@ -401,42 +426,74 @@ __global__ __launch_bounds__(256) void train_kernel(TrainArgs a)
 }
 
 // ---------------------------------------------------------------------------------------------
-// apply kernel: table[row] += slot, slot = 0 for every shared row; then empty the hash set.
-// 16 lanes per shared row, grid-stride over the list.
+// apply kernel: one thread per row reference.  The reference that owns a hash position empties it;
+// the block then collects the shared rows among its positions in LDS and 16-lane groups add each
+// row's slot to the table row and zero the slot.
 // ---------------------------------------------------------------------------------------------
 struct ApplyArgs {
     float4* X;
     float4* C;
     int32_t d4;
     float4* delta;
-    const uint2* dup_list;
-    uint32_t* n_dup;        // this batch's count (read)
-    uint32_t* n_dup_next;   // next batch's count (reset to 0)
-    uint32_t* keys;
-    uint32_t* dupbits;
-    uint32_t cap;
+    int64_t refs;
+    int32_t R;
+    const int32_t* ids;
+    const uint32_t* posbuf;
+    unsigned long long* slots;
+    uint8_t* shared;
 };
 
 __global__ __launch_bounds__(256) void apply_kernel(ApplyArgs a)
 {
-    const uint32_t n = *a.n_dup;
-    const int lg = threadIdx.x & 15;
-    const uint32_t groups_total = gridDim.x * 16u;
-    for (uint32_t i = blockIdx.x * 16u + (threadIdx.x >> 4); i < n; i += groups_total) {
-        const uint2 e = a.dup_list[i];
-        float4* row = ((e.y & 0x80000000u) ? a.C : a.X) + static_cast<int64_t>(e.y & 0x7FFFFFFFu) * a.d4;
-        float4* slot = a.delta + static_cast<int64_t>(e.x) * a.d4;
-        for (int ci = lg; ci < a.d4; ci += 16) {
-            const float4 v = slot[ci];
-            const float4 t = row[ci];
-            row[ci] = make_float4(t.x + v.x, t.y + v.y, t.z + v.z, t.w + v.w);
-            slot[ci] = make_float4(0.f, 0.f, 0.f, 0.f);
+    __shared__ uint2 todo_list[256];   // (position, key) of the shared rows this block applies
+    __shared__ int todo_count;
+    if (threadIdx.x == 0) todo_count = 0;
+    __syncthreads();
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    bool todo = false;
+    uint32_t pos = 0, key = 0;
+    if (t < a.refs) {
+        const uint32_t p = a.posbuf[t];
+        if (p & 0x80000000u) {
+            pos = p & kPosMask;
+            todo = a.shared[pos] != 0;
+            if (todo) a.shared[pos] = 0;
+            a.slots[pos] = kEmptySlot;
+            if (todo) key = static_cast<uint32_t>(a.ids[t]) | ((t % a.R) != 0 ? 0x80000000u : 0u);
         }
     }
-    const uint32_t stride = gridDim.x * 256u;
-    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < a.cap; i += stride) a.keys[i] = kEmptyKey;
-    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < a.cap / 32; i += stride) a.dupbits[i] = 0u;
-    if (blockIdx.x == 0 && threadIdx.x == 0) *a.n_dup_next = 0u;
+    const uint64_t votes = __ballot(todo);
+    if (votes) {
+        const int lane = threadIdx.x & 63;
+        const int leader = __ffsll(static_cast<long long>(votes)) - 1;
+        int base = 0;
+        if (lane == leader) base = atomicAdd(&todo_count, static_cast<int>(__popcll(votes)));
+        base = __shfl(base, leader, 64);
+        if (todo) todo_list[base + static_cast<int>(__popcll(votes & ((1ull << lane) - 1ull)))] = make_uint2(pos, key);
+    }
+    __syncthreads();
+    const int n = todo_count;
+    const int lg = threadIdx.x & 15;
+    for (int e = threadIdx.x >> 4; e < n; e += 16) {
+        const uint2 item = todo_list[e];
+        float4* row = ((item.y & 0x80000000u) ? a.C : a.X) + static_cast<int64_t>(item.y & 0x7FFFFFFFu) * a.d4;
+        float4* slot = a.delta + static_cast<int64_t>(item.x) * a.d4;
+        for (int c0 = 0; c0 < a.d4; c0 += 32) {
+            const int ca = c0 + lg, cb = c0 + 16 + lg;
+            const bool va = ca < a.d4, vb = cb < a.d4;
+            float4 sa, sb, ra, rb;
+            if (va) { sa = slot[ca]; ra = row[ca]; }
+            if (vb) { sb = slot[cb]; rb = row[cb]; }
+            if (va) {
+                row[ca] = make_float4(ra.x + sa.x, ra.y + sa.y, ra.z + sa.z, ra.w + sa.w);
+                slot[ca] = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+            if (vb) {
+                row[cb] = make_float4(rb.x + sb.x, rb.y + sb.y, rb.z + sb.z, rb.w + sb.w);
+                slot[cb] = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -589,17 +646,17 @@ bool workspace_layout(int32_t dim, int64_t max_B, int32_t max_K, char* base, Wor
         return false;
     const uint64_t refs = static_cast<uint64_t>(max_B) * (max_K + 2);
     uint64_t cap = 1024;
-    while (cap < 2 * refs) cap <<= 1;
+    while (cap < 4 * refs) cap <<= 1;
     auto up = [](size_t v) { return (v + 255) & ~static_cast<size_t>(255); };
     size_t off = 0;
     auto take = [&](size_t bytes) { char* p = base + off; off = up(off + bytes); return p; };
     w->cap = static_cast<uint32_t>(cap);
-    w->keys = reinterpret_cast<uint32_t*>(take(cap * 4));
-    w->dupbits = reinterpret_cast<uint32_t*>(take(cap / 32 * 4));
-    w->counters = reinterpret_cast<uint32_t*>(take(16));
-    w->dup_list = reinterpret_cast<uint2*>(take(cap / 4 * sizeof(uint2)));
-    w->ids = reinterpret_cast<int32_t*>(take(refs * 4));
-    w->posbuf = reinterpret_cast<uint32_t*>(take(refs * 4));
+    for (int i = 0; i < 2; ++i) {
+        w->prep[i].slots = reinterpret_cast<unsigned long long*>(take(cap * 8));
+        w->prep[i].shared = reinterpret_cast<uint8_t*>(take(cap));
+        w->prep[i].ids = reinterpret_cast<int32_t*>(take(refs * 4));
+        w->prep[i].posbuf = reinterpret_cast<uint32_t*>(take(refs * 4));
+    }
     w->delta = reinterpret_cast<float*>(take(cap * static_cast<size_t>(dim) * 4));
     w->total_bytes = off;
     return true;
@@ -663,6 +720,7 @@ ne_status ne_create_tables(ne_tables** out, int64_t num_nodes, int32_t dim, floa
     if (!t) return fail(NE_ERR_NOMEM, "host allocation failed");
     t->num_nodes = num_nodes; t->dim = dim; t->vertex = vertex_dev; t->context = context_dev; t->seed = seed;
     t->max_batch = 0; t->max_negatives = 0; t->batches_done = 0; t->profile_every = 0; t->ev_used = 0;
+    t->prepared[0] = {0, 0, false}; t->prepared[1] = {0, 0, false};
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
 
     if (workspace_dev || max_batch > 0) {   // training requested
@@ -676,9 +734,11 @@ ne_status ne_create_tables(ne_tables** out, int64_t num_nodes, int32_t dim, floa
             return fail(NE_ERR_ARG, "workspace_dev is NULL, not 256-byte aligned, or smaller than ne_workspace_bytes()");
         }
         t->ws = w; t->max_batch = max_batch; t->max_negatives = max_negatives;
-        hipError_t e = launch_fill(w.keys, w.cap, kEmptyKey, st);
-        if (e == hipSuccess) e = launch_fill(w.dupbits, w.cap / 32, 0u, st);
-        if (e == hipSuccess) e = launch_fill(w.counters, 4, 0u, st);
+        hipError_t e = hipSuccess;
+        for (int i = 0; i < 2 && e == hipSuccess; ++i) {
+            e = launch_fill(reinterpret_cast<uint32_t*>(w.prep[i].slots), static_cast<size_t>(w.cap) * 2, 0xFFFFFFFFu, st);
+            if (e == hipSuccess) e = launch_fill(reinterpret_cast<uint32_t*>(w.prep[i].shared), w.cap / 4, 0u, st);
+        }
         if (e == hipSuccess) e = launch_fill(reinterpret_cast<uint32_t*>(w.delta), static_cast<size_t>(w.cap) * dim, 0u, st);
         if (e != hipSuccess) {
             delete t;
@@ -811,42 +871,64 @@ ne_status ne_build_neg_alias(ne_alias** out, const uint32_t* degree_host, int64_
     return NE_OK;
 }
 
-ne_status ne_train_batch(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t B, int32_t K,
-                         float lr, uint64_t sample_base, int32_t* neg_out_dev, void* hip_stream)
+ne_status ne_prepare_batch(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t B, int32_t K,
+                           uint64_t sample_base, int32_t* neg_out_dev, int32_t slot, void* hip_stream)
 {
     Shape shape;
     ne_status rc = check_batch_args(t, al, pairs_dev, B, K, &shape);
     if (rc != NE_OK) return rc;
-    if (!std::isfinite(lr)) return fail(NE_ERR_ARG, "lr is not finite");
+    if (slot < 0 || slot > 1) return fail(NE_ERR_ARG, "slot must be 0 or 1");
     if (t->max_batch <= 0) return fail(NE_ERR_STATE, "tables were created without a training workspace");
     if (B > t->max_batch || K > t->max_negatives)
         return fail(NE_ERR_ARG, "B or K exceeds the max_batch / max_negatives the workspace was sized for");
+    if (t->prepared[slot].ready) return fail(NE_ERR_STATE, "slot holds a prepared batch that was not trained yet");
+    t->prepared[slot] = {B, K, true};
     if (B == 0) return NE_OK;
 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const Workspace& w = t->ws;
-    const unsigned parity = static_cast<unsigned>(t->batches_done & 1);
-
+    const PrepSlot& ps = w.prep[slot];
     PrepArgs pa{};
     pa.pairs = reinterpret_cast<const int2*>(pairs_dev);
     pa.B = B; pa.K = K; pa.sample_base = sample_base;
     pa.k0 = static_cast<uint32_t>(t->seed); pa.k1 = static_cast<uint32_t>(t->seed >> 32);
     pa.alias = al ? al->table : nullptr; pa.alias_n = al ? static_cast<uint64_t>(al->n) : 1; pa.alias_base = al ? al->base : 0;
-    pa.keys = w.keys; pa.mask = w.cap - 1; pa.dupbits = w.dupbits; pa.n_dup = w.counters + parity;
-    pa.dup_list = w.dup_list; pa.ids = w.ids; pa.posbuf = w.posbuf; pa.neg_out = neg_out_dev;
-    const int64_t refs = B * (K + 2);
-    hipLaunchKernelGGL(prep_kernel, dim3(static_cast<unsigned>((refs + 255) / 256)), dim3(256), 0, st, pa);
+    pa.slots = ps.slots; pa.mask = w.cap - 1; pa.shared = ps.shared; pa.ids = ps.ids; pa.posbuf = ps.posbuf;
+    pa.neg_out = neg_out_dev;
+    const unsigned grid = static_cast<unsigned>((B * (K + 2) + 255) / 256);
+    hipLaunchKernelGGL(claim_kernel, dim3(grid), dim3(256), 0, st, pa);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("prep launch: ") + hipGetErrorString(e));
+    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("claim launch: ") + hipGetErrorString(e));
+    hipLaunchKernelGGL(resolve_kernel, dim3(grid), dim3(256), 0, st, pa);
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("resolve launch: ") + hipGetErrorString(e));
+    return NE_OK;
+}
 
+ne_status ne_train_prepared(ne_tables* t, int32_t slot, float lr, void* hip_stream)
+{
+    if (!t) return fail(NE_ERR_ARG, "tables handle is NULL");
+    if (slot < 0 || slot > 1) return fail(NE_ERR_ARG, "slot must be 0 or 1");
+    if (!std::isfinite(lr)) return fail(NE_ERR_ARG, "lr is not finite");
+    if (!t->prepared[slot].ready) return fail(NE_ERR_STATE, "no prepared batch in this slot");
+    const int64_t B = t->prepared[slot].B;
+    const int32_t K = t->prepared[slot].K;
+    t->prepared[slot].ready = false;
+    if (B == 0) return NE_OK;
+    Shape shape;
+    if (!pick_shape(t->dim / 4, K, &shape)) return fail(NE_ERR_ARG, "no launch shape for this (dim, K)");
+
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const Workspace& w = t->ws;
+    const PrepSlot& ps = w.prep[slot];
     TrainArgs ta{};
     ta.X = reinterpret_cast<float4*>(t->vertex); ta.C = reinterpret_cast<float4*>(t->context);
     ta.B = B; ta.K = K; ta.d4 = t->dim / 4; ta.lr = lr;
-    ta.ids = w.ids; ta.posbuf = w.posbuf; ta.dupbits = w.dupbits; ta.delta = w.delta;
+    ta.ids = ps.ids; ta.posbuf = ps.posbuf; ta.shared = ps.shared; ta.delta = w.delta;
     const bool timed = t->profile_every > 0 && t->batches_done % static_cast<uint64_t>(t->profile_every) == 0 &&
                        t->ev_used < t->ev_start.size();
     if (timed) NE_HIP_CHECK(hipEventRecord(t->ev_start[t->ev_used], st));
-    e = launch_train(shape, ta, st);
+    hipError_t e = launch_train(shape, ta, st);
     if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("train launch: ") + hipGetErrorString(e));
     if (timed) {
         NE_HIP_CHECK(hipEventRecord(t->ev_stop[t->ev_used], st));
@@ -855,14 +937,23 @@ ne_status ne_train_batch(ne_tables* t, const ne_alias* al, const int32_t* pairs_
 
     ApplyArgs aa{};
     aa.X = ta.X; aa.C = ta.C; aa.d4 = ta.d4; aa.delta = reinterpret_cast<float4*>(w.delta);
-    aa.dup_list = w.dup_list; aa.n_dup = w.counters + parity; aa.n_dup_next = w.counters + (parity ^ 1);
-    aa.keys = w.keys; aa.dupbits = w.dupbits; aa.cap = w.cap;
-    const unsigned apply_grid = static_cast<unsigned>(w.cap / 256 < 2048 ? w.cap / 256 : 2048);
-    hipLaunchKernelGGL(apply_kernel, dim3(apply_grid), dim3(256), 0, st, aa);
+    aa.refs = B * (K + 2); aa.R = K + 2; aa.ids = ps.ids; aa.posbuf = ps.posbuf; aa.slots = ps.slots; aa.shared = ps.shared;
+    hipLaunchKernelGGL(apply_kernel, dim3(static_cast<unsigned>((aa.refs + 255) / 256)), dim3(256), 0, st, aa);
     e = hipGetLastError();
     if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("apply launch: ") + hipGetErrorString(e));
     t->batches_done += 1;
     return NE_OK;
+}
+
+ne_status ne_train_batch(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t B, int32_t K,
+                         float lr, uint64_t sample_base, int32_t* neg_out_dev, void* hip_stream)
+{
+    if (!std::isfinite(lr)) return fail(NE_ERR_ARG, "lr is not finite");
+    if (t && (t->prepared[0].ready || t->prepared[1].ready))
+        return fail(NE_ERR_STATE, "a batch prepared with ne_prepare_batch is still pending");
+    ne_status rc = ne_prepare_batch(t, al, pairs_dev, B, K, sample_base, neg_out_dev, 0, hip_stream);
+    if (rc != NE_OK) return rc;
+    return ne_train_prepared(t, 0, lr, hip_stream);
 }
 
 ne_status ne_eval_loss(const ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t B, int32_t K,

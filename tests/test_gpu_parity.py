@@ -194,3 +194,54 @@ def test_empty_batch_and_validate():
         t2 = torch.empty((200, 2), dtype=torch.int32, device="cuda:0")
         a2 = ne.ne_build_neg_alias(np.ones(200, np.uint32), 0, t2)
         ne.ne_train_batch(m.tables, a2, pairs[:1], K, 0.1, 0)
+
+
+def test_two_stream_pipeline_matches_oracle():
+    """ne_prepare_batch of batch t+1 on a second stream while batch t trains (two slots)."""
+    say("two-stream pipeline")
+    V, d, K, B, seed, nb = 6000, 128, 5, 2048, 3, 12
+    rng = np.random.default_rng(1)
+    deg = (rng.pareto(1.0, V) * 2).astype(np.uint32) + 1
+    m = GpuModel(V, d, seed, deg, K, B)
+    Xo, Co = oracle.init_tables(V, d, seed)
+    Xo[:] = rng.normal(0, 0.2, Xo.shape).astype(np.float32)
+    Co[:] = rng.normal(0, 0.2, Co.shape).astype(np.float32)
+    m.vertex.copy_(torch.from_numpy(Xo)); m.context.copy_(torch.from_numpy(Co))
+    thr, alias, _ = oracle.build_alias(deg)
+    ids = np.minimum((rng.pareto(0.8, (nb, B, 2)) * V / 50).astype(np.int64), V - 1).astype(np.int32)
+    pairs_dev = torch.from_numpy(ids).cuda()
+    negs = [torch.empty((B, K), dtype=torch.int32, device="cuda:0") for _ in range(nb)]
+    torch.cuda.synchronize()
+    s_prep, s_train = torch.cuda.Stream(), torch.cuda.Stream()
+    prepared = [torch.cuda.Event() for _ in range(nb)]
+    trained = [torch.cuda.Event() for _ in range(nb)]
+    for t in range(nb + 1):
+        if t < nb:
+            if t >= 2:
+                s_prep.wait_event(trained[t - 2])        # the slot is free again
+            ne.ne_prepare_batch(m.tables, m.alias, pairs_dev[t], K, t * B, t & 1, negs[t], stream=s_prep)
+            prepared[t].record(s_prep)
+        if t >= 1:
+            u = t - 1
+            s_train.wait_event(prepared[u])
+            ne.ne_train_prepared(m.tables, u & 1, 0.05, stream=s_train)
+            trained[u].record(s_train)
+    torch.cuda.synchronize()
+    for t in range(nb):
+        neg_o = oracle.sample_negatives(seed, t * B, B, K, thr, alias)
+        assert np.array_equal(negs[t].cpu().numpy(), neg_o)
+        oracle.train_batch(Xo, Co, ids[t], neg_o, 0.05)
+    Xg, Cg = m.host_tables()
+    ex, ec = rowwise_rel_err(Xg, Xo), rowwise_rel_err(Cg, Co)
+    say(f"  rowwise err X {ex:.2e} C {ec:.2e}")
+    assert ex <= 1e-3 and ec <= 1e-3
+    # slot protocol errors are reported, not executed
+    with pytest.raises(ne.NeError):
+        ne.ne_train_prepared(m.tables, 0, 0.05)
+    ne.ne_prepare_batch(m.tables, m.alias, pairs_dev[0], K, 0, 1)
+    with pytest.raises(ne.NeError):
+        ne.ne_prepare_batch(m.tables, m.alias, pairs_dev[0], K, 0, 1)
+    with pytest.raises(ne.NeError):
+        ne.ne_train_batch(m.tables, m.alias, pairs_dev[0], K, 0.05, 0)
+    ne.ne_train_prepared(m.tables, 1, 0.0)
+    torch.cuda.synchronize()
