@@ -88,8 +88,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="c3", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-pipeline", action="store_true", help="one stream, ne_train_batch per step")
+    ap.add_argument("--per-batch", action="store_true", help="one library call per batch (no fused prepare)")
     ap.add_argument("--cpu-batches", type=int, default=0, help="oracle batches to time (0 = auto)")
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (experiments)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -101,6 +102,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     name = args.workload
+    if args.batch > 0:
+        WORKLOADS[name] = dict(WORKLOADS[name], B=args.batch)
     n_batches = args.steps + args.warmup
     w, degree, bp, sched = build_workload(name, n_batches, dev)
     V, d, K, B, grid, seed = w["V"], w["d"], w["K"], w["B"], w["grid"], w["seed"]
@@ -126,30 +129,20 @@ def main():
     lrs = [np.float32(wl.linear_decay_lr(0.025, i * B, total_pairs)) for i in range(n_batches)]
     pairs = bp.pairs
 
-    s_prep, s_train = torch.cuda.Stream(), torch.cuda.Stream()
-
     def run(first, last):
-        """Batches [first, last): the id-only half of batch i+1 (negative sampling, shared-row
-        detection) runs on s_prep while batch i trains on s_train; two preparation slots."""
-        if args.no_pipeline:
-            for i in range(first, last):
-                s, n, _, j = sched[i]
-                ne.ne_train_batch(tables, aliases[j], pairs[s:s + n], K, float(lrs[i]), i * B, stream=s_train)
-            return
-        prepared = [torch.cuda.Event() for _ in range(2)]
-        trained = [torch.cuda.Event() for _ in range(2)]
-        for i in range(first, last + 1):
-            if i < last:
-                if i - 2 >= first:
-                    s_prep.wait_event(trained[i & 1])          # slot i&1 was released by batch i-2
-                s, n, _, j = sched[i]
-                ne.ne_prepare_batch(tables, aliases[j], pairs[s:s + n], K, i * B, i & 1, stream=s_prep)
-                prepared[i & 1].record(s_prep)
-            if i - 1 >= first:
-                u = i - 1
-                s_train.wait_event(prepared[u & 1])
-                ne.ne_train_prepared(tables, u & 1, float(lrs[u]), stream=s_train)
-                trained[u & 1].record(s_train)
+        """Batches [first, last).  Consecutive batches of one (src-block, ctx-block) bucket go to the
+        library as one ne_train_block call (the id-only work of batch i+1 then rides in the kernels
+        of batch i); --per-batch calls ne_train_batch once per batch instead."""
+        i = first
+        while i < last:
+            s, n, bi, bj = sched[i]
+            k = i + 1
+            if not args.per_batch:
+                while k < last and sched[k][2:] == (bi, bj) and sched[k][0] == sched[k - 1][0] + B:
+                    k += 1
+            count = k - i
+            ne.ne_train_block(tables, aliases[bj], pairs[s:s + count * B], B, K, lrs[i:k], i * B)
+            i = k
 
     torch.cuda.synchronize()
     run(0, args.warmup)
@@ -180,7 +173,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": name, "nodes": V, "dim": d, "negatives": K, "batch": B, "block_grid": f"{grid}x{grid}",
-                   "streams": 1 if args.no_pipeline else 2,
+                   "call": "ne_train_batch per step" if args.per_batch else "ne_train_block per bucket run",
                    "end_to_end_GBps": pairs_per_s * bpp / 1e9},
         "roofline": {"bound": "hbm", "kernel": "train_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": (achieved / HBM_PEAK_GBS) if achieved else None,

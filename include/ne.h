@@ -109,25 +109,21 @@ ne_status ne_train_batch(ne_tables* tables, const ne_alias* alias, const int32_t
                          void* hip_stream);
 
 /*
- * The same step in two halves, for callers that overlap the id-only half of batch t+1 with the
- * table-touching half of batch t on two streams.
- *
- * ne_prepare_batch draws the negatives of the batch and finds out which table rows more than one
- * of its (src, ctx, negative) references name (Algorithm 1: EdgeSample and NegativeSample).  It reads
- * pairs_dev and the alias table, writes only the handle's workspace (preparation slot `slot`, 0 or 1)
- * and neg_out_dev, and never touches the embedding tables.  Arguments as for ne_train_batch.
- *
- * ne_train_prepared scores the prepared batch and applies its update (Algorithm 1: the Train calls),
- * then releases the slot.  It must be ordered after the ne_prepare_batch of the same slot (same
- * stream, or an event the caller records and waits on), and after every earlier ne_train_prepared on
- * the same handle.  A slot can hold one batch: prepare - train - prepare - ...; the next
- * ne_prepare_batch of a slot must be ordered after the ne_train_prepared that used it.
- * Errors: NE_ERR_ARG, NE_ERR_STATE (slot busy / nothing prepared), NE_ERR_HIP.
+ * Train on a run of consecutive batches: the n_pairs samples of pairs_dev in batches of B (the last
+ * one may be shorter), i.e. ceil(n_pairs / B) iterations of the embedding-training loop of
+ * Algorithm 1 on one sample block with one negative-sampling table (Sec. III-C: a GPU trains its
+ * vertex embeddings on a sample block against its fixed context partition).  The result is the same
+ * as calling ne_train_batch once per batch with lr = lr_host[i] and sample_base + i*B; the call
+ * exists because the id-only work of batch i+1 (negative draws, detection of rows named more than
+ * once) then runs inside the kernels of batch i: two kernel launches per batch instead of four.
+ *   pairs_dev   : device, int32[n_pairs][2]; must stay unchanged until the enqueued work is done.
+ *   lr_host     : host, float[ceil(n_pairs / B)], read during the call only.
+ *   neg_out_dev : NULL, or device int32[n_pairs][K].
+ * Other arguments, semantics and errors as for ne_train_batch.  n_pairs == 0 is a no-op.
  */
-ne_status ne_prepare_batch(ne_tables* tables, const ne_alias* alias, const int32_t* pairs_dev, int64_t B,
-                           int32_t K, uint64_t sample_base, int32_t* neg_out_dev, int32_t slot,
-                           void* hip_stream);
-ne_status ne_train_prepared(ne_tables* tables, int32_t slot, float lr, void* hip_stream);
+ne_status ne_train_block(ne_tables* tables, const ne_alias* alias, const int32_t* pairs_dev,
+                         int64_t n_pairs, int64_t B, int32_t K, const float* lr_host,
+                         uint64_t sample_base, int32_t* neg_out_dev, void* hip_stream);
 
 /*
  * Loss of a batch at the current tables with the same negatives ne_train_batch would draw; nothing

@@ -25,8 +25,8 @@ NE_MAX_NEGATIVES = 62
 NE_MAX_BATCH = 1 << 22
 
 EXPORTS = (
-    "ne_create_tables", "ne_build_neg_alias", "ne_workspace_bytes", "ne_train_batch", "ne_prepare_batch",
-    "ne_train_prepared", "ne_eval_loss",
+    "ne_create_tables", "ne_build_neg_alias", "ne_workspace_bytes", "ne_train_batch", "ne_train_block",
+    "ne_eval_loss",
     "ne_validate_pairs", "ne_profile_enable", "ne_profile_read", "ne_destroy_tables", "ne_destroy_alias", "ne_last_error",
 )
 
@@ -59,10 +59,8 @@ def lib() -> ctypes.CDLL:
     L.ne_workspace_bytes.restype = c.c_size_t
     L.ne_train_batch.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_float, c.c_uint64, vp, vp]
     L.ne_train_batch.restype = c.c_int
-    L.ne_prepare_batch.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_uint64, vp, c.c_int32, vp]
-    L.ne_prepare_batch.restype = c.c_int
-    L.ne_train_prepared.argtypes = [vp, c.c_int32, c.c_float, vp]
-    L.ne_train_prepared.restype = c.c_int
+    L.ne_train_block.argtypes = [vp, vp, vp, c.c_int64, c.c_int64, c.c_int32, c.POINTER(c.c_float), c.c_uint64, vp, vp]
+    L.ne_train_block.restype = c.c_int
     L.ne_eval_loss.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_uint64, vp, vp, vp]
     L.ne_eval_loss.restype = c.c_int
     L.ne_validate_pairs.argtypes = [vp, vp, c.c_int64, vp, vp]
@@ -185,22 +183,20 @@ def ne_train_batch(tables: Tables, alias: Alias | None, pairs: torch.Tensor, K: 
                                 np_, _stream_ptr(stream)))
 
 
-def ne_prepare_batch(tables: Tables, alias: Alias | None, pairs: torch.Tensor, K: int, sample_base: int,
-                     slot: int, neg_out: torch.Tensor | None = None, stream=None, B: int | None = None) -> None:
-    """Id-only half of a step (negatives + shared-row detection) into preparation slot 0 or 1."""
-    if B is None:
-        B = int(pairs.shape[0])
+def ne_train_block(tables: Tables, alias: Alias | None, pairs: torch.Tensor, B: int, K: int, lrs,
+                   sample_base: int, neg_out: torch.Tensor | None = None, stream=None) -> None:
+    """All of pairs int32 [n_pairs][2] (CUDA) in consecutive batches of B; lrs: one float per batch."""
+    n_pairs = int(pairs.shape[0])
+    n_batches = -(-n_pairs // B) if B > 0 else 0
+    if len(lrs) < n_batches:
+        raise TypeError("lrs needs one learning rate per batch")
+    arr = (ctypes.c_float * max(n_batches, 1))(*[float(v) for v in lrs[:n_batches]])
     pp = _dev_ptr(pairs, torch.int32, "pairs")
     np_ = _dev_ptr(neg_out, torch.int32, "neg_out")
-    if neg_out is not None and neg_out.numel() < B * K:
-        raise TypeError("neg_out needs B*K int32 elements")
-    _check(lib().ne_prepare_batch(tables.handle, alias.handle if alias else None, pp, B, K, sample_base, np_, slot,
-                                  _stream_ptr(stream)))
-
-
-def ne_train_prepared(tables: Tables, slot: int, lr: float, stream=None) -> None:
-    """Table-touching half of a step for the batch prepared in `slot`."""
-    _check(lib().ne_train_prepared(tables.handle, slot, lr, _stream_ptr(stream)))
+    if neg_out is not None and neg_out.numel() < n_pairs * K:
+        raise TypeError("neg_out needs n_pairs*K int32 elements")
+    _check(lib().ne_train_block(tables.handle, alias.handle if alias else None, pp, n_pairs, B, K, arr, sample_base,
+                                np_, _stream_ptr(stream)))
 
 
 def ne_eval_loss(tables: Tables, alias: Alias | None, pairs: torch.Tensor, K: int, sample_base: int,

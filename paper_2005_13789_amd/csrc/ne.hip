@@ -1,29 +1,33 @@
 // SGNS node-embedding training for MI355X (gfx950): HIP kernels and the C ABI declared in ne.h.
 //
-// One batch of the embedding-training loop (Algorithm 1; Sec. II-A "Training Process") is four
-// kernels:
+// One batch of the embedding-training loop (Algorithm 1; Sec. II-A "Training Process") has four
+// phases:
 //
-//   claim, resolve (ids only; ne_prepare_batch)  one thread per row reference (src, ctx and the K
-//          negatives of every pair).  claim draws the negative (Philox + alias table) and stores
-//          (key, reference index) at the key's hash position with a plain 8-byte store; whichever
-//          store lands last owns the position.  resolve reads the position back: a reference whose
-//          key owns it but whose index differs has found a second reference of the same row and
-//          flags the row as shared; references whose key lost the position (a different row hashed
-//          there) fall back to compare-and-swap probing.  Returning atomics retire slowly on this
-//          chip, so only that minority uses them.
-//   train  (ne_train_prepared) one lane group per pair: gathers x = vertex[src] and the K+1 context
-//          rows (dwordx4), reduces the K+1 dot products with DPP, forms g_j and the deltas.  A row
-//          that only this pair names is rewritten in place from registers (old + delta, one plain
-//          store: the row costs one read and one write).  A shared row is left untouched - other
-//          pairs must still read its pre-batch value - and its delta is added to the row's slot
-//          (indexed by hash position) with fp32 atomics.
-//   apply  adds each shared row's slot to the table row, zeroes the slot and empties the hash table.
+//   claim, resolve (ids only)  one thread per row reference (src, ctx and the K negatives of every
+//          pair).  claim draws the negative (Philox + alias table) and stores (key, reference
+//          index) at the key's hash position with a plain 8-byte store; whichever store lands last
+//          owns the position.  resolve reads the position back: a reference whose key owns it but
+//          whose index differs has found a second reference of the same row and flags the row as
+//          shared; references whose key lost the position (a different row hashed there) fall back
+//          to compare-and-swap probing.  Returning atomics retire slowly on this chip, so only that
+//          minority uses them.
+//   train  one lane group per pair: gathers x = vertex[src] and the K+1 context rows (dwordx4),
+//          reduces the K+1 dot products with DPP, forms g_j and the deltas.  A row that only this
+//          pair names is rewritten in place from registers (old + delta, one plain store: the row
+//          costs one read and one write).  A shared row is left untouched - other pairs must still
+//          read its pre-batch value - and its delta is added to the row's slot (indexed by hash
+//          position) with fp32 atomics.
+//   apply  adds each shared row's slot to the table row and zeroes the slot; the hash positions of
+//          the batch are emptied.
 //
 // This is exactly minibatch-synchronous: no row that a second reference could read is written
-// before the apply kernel, and all contributions to a row are summed.  fp32 atomics on gfx950
+// before the apply phase, and all contributions to a row are summed.  fp32 atomics on gfx950
 // retire one dword per L2 channel clock, far below the rate of plain row stores, which is why only
-// shared rows go through them.  The id-only kernels of batch t+1 do not touch the tables, so a
-// caller may run them on a second stream while batch t trains (two preparation slots).
+// shared rows go through them.
+//
+// claim and resolve never touch the tables, so for a run of batches (ne_train_block) they ride
+// along in the kernels of the batch before: kernel A = train(t) + claim(t+1), kernel B = apply(t) +
+// resolve(t+1), two launches per batch, with two sets of hash state used alternately.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -62,8 +66,7 @@ struct PrepSlot {
     unsigned long long* slots;  // [cap]  (key << 32 | reference index) per hash position; ~0 = empty
     uint8_t* shared;            // [cap]  1 <=> the row whose key sits at this position is shared
     int32_t* ids;               // [max_B][max_K+2]  src, ctx, negatives
-    uint32_t* posbuf;           // [max_B][max_K+2]  final hash position; bit 31: this reference
-                                //                   cleans up (and applies) the position
+    uint32_t* posbuf;           // [max_B][max_K+2]  final hash position of each reference
 };
 struct Workspace {
     PrepSlot prep[2];
@@ -84,7 +87,6 @@ struct ne_tables {
     int32_t max_negatives;
     Workspace ws;
     uint64_t batches_done;
-    struct { int64_t B; int32_t K; bool ready; } prepared[2];
     // optional timing of the train kernel with HIP events (ne_profile_enable / ne_profile_read)
     int32_t profile_every;
     std::vector<hipEvent_t> ev_start, ev_stop;
@@ -211,13 +213,12 @@ __global__ __launch_bounds__(256) void init_tables_kernel(float4* __restrict__ X
 // key = row | (context table ? 1 << 31 : 0).
 // ---------------------------------------------------------------------------------------------
 constexpr unsigned long long kEmptySlot = ~0ull;
-constexpr uint32_t kPosMask = 0x7FFFFFFFu;
 
 __device__ __forceinline__ uint32_t hash_key(uint32_t key, uint32_t mask) { return ((key * 0x9E3779B1u) >> 7) & mask; }
 
 struct PrepArgs {
     const int2* pairs;
-    int64_t B;
+    uint32_t refs;        // B * (K + 2); 0 = nothing to prepare
     int32_t K;
     uint64_t sample_base;
     uint32_t k0, k1;
@@ -232,56 +233,107 @@ struct PrepArgs {
     int32_t* neg_out;
 };
 
-__global__ __launch_bounds__(256) void claim_kernel(PrepArgs a)
+// Both phases are chains of dependent memory accesses with next to no arithmetic, so each thread
+// runs kPrepUnroll references at once: a block covers 256 * kPrepUnroll consecutive references.
+constexpr int kPrepUnroll = 4;
+
+__device__ __forceinline__ void claim_refs(const PrepArgs& a, unsigned block)
 {
-    const int R = a.K + 2;
-    const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (t >= a.B * R) return;
-    const int64_t b = t / R;
-    const int j = static_cast<int>(t - b * R);
-    int32_t id;
-    if (j < 2) {
-        const int2 pr = a.pairs[b];
-        id = j == 0 ? pr.x : pr.y;
-    } else {
-        id = draw_negative(a.sample_base + static_cast<uint64_t>(b), static_cast<uint32_t>(j - 2), a.k0, a.k1, a.alias,
-                           a.alias_n, a.alias_base);
-        if (a.neg_out) a.neg_out[b * a.K + (j - 2)] = id;
+    const uint32_t R = static_cast<uint32_t>(a.K + 2);
+    uint32_t t[kPrepUnroll], b[kPrepUnroll];
+    int j[kPrepUnroll];
+    int32_t id[kPrepUnroll];
+    uint4 rnd[kPrepUnroll];
+    uint2 entry[kPrepUnroll];
+    uint64_t draw_slot[kPrepUnroll];
+#pragma unroll
+    for (int u = 0; u < kPrepUnroll; ++u) {
+        t[u] = (block * kPrepUnroll + u) * 256u + threadIdx.x;
+        b[u] = t[u] / R;
+        j[u] = static_cast<int>(t[u] - b[u] * R);
+        id[u] = 0;
+        if (t[u] < a.refs) {
+            if (j[u] < 2) {
+                const int2 pr = a.pairs[b[u]];
+                id[u] = j[u] == 0 ? pr.x : pr.y;
+            } else {
+                const uint64_t sample = a.sample_base + b[u];
+                rnd[u] = philox4x32_10(make_uint4(static_cast<uint32_t>(sample), static_cast<uint32_t>(sample >> 32),
+                                                  static_cast<uint32_t>(j[u] - 2), kStreamNegative), a.k0, a.k1);
+                draw_slot[u] = __umul64hi((static_cast<uint64_t>(rnd[u].x) << 32) | rnd[u].y, a.alias_n);
+                entry[u] = a.alias[draw_slot[u]];
+            }
+        }
     }
-    a.ids[t] = id;
-    const uint32_t key = static_cast<uint32_t>(id) | (j == 0 ? 0u : 0x80000000u);
-    a.slots[hash_key(key, a.mask)] = (static_cast<unsigned long long>(key) << 32) | static_cast<uint32_t>(t);
+#pragma unroll
+    for (int u = 0; u < kPrepUnroll; ++u) {
+        if (t[u] < a.refs) {
+            if (j[u] >= 2) {
+                id[u] = a.alias_base + static_cast<int32_t>(rnd[u].z < entry[u].x ? static_cast<uint32_t>(draw_slot[u]) : entry[u].y);
+                if (a.neg_out) a.neg_out[static_cast<int64_t>(b[u]) * a.K + (j[u] - 2)] = id[u];
+            }
+            a.ids[t[u]] = id[u];
+            const uint32_t key = static_cast<uint32_t>(id[u]) | (j[u] == 0 ? 0u : 0x80000000u);
+            a.slots[hash_key(key, a.mask)] = (static_cast<unsigned long long>(key) << 32) | t[u];
+        }
+    }
 }
 
-__global__ __launch_bounds__(256) void resolve_kernel(PrepArgs a)
+__device__ __forceinline__ void resolve_refs(const PrepArgs& a, unsigned block)
 {
-    const int R = a.K + 2;
-    const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (t >= a.B * R) return;
-    const int j = static_cast<int>(t % R);
-    const uint32_t key = static_cast<uint32_t>(a.ids[t]) | (j == 0 ? 0u : 0x80000000u);
-    uint32_t pos = hash_key(key, a.mask);
-    const unsigned long long owner = a.slots[pos];
-    if (static_cast<uint32_t>(owner >> 32) == key) {
-        // my row owns its home position; the reference whose store landed last cleans up
-        if (static_cast<uint32_t>(owner) == static_cast<uint32_t>(t)) {
-            pos |= 0x80000000u;
-        } else {
-            a.shared[pos] = 1;
-        }
-    } else {
-        // another row owns the home position: probe onwards.  Positions only ever go from empty to
-        // occupied here, and the table holds at most cap/4 keys, so the walk ends.
-        const unsigned long long mine = (static_cast<unsigned long long>(key) << 32) | static_cast<uint32_t>(t);
-        while (true) {
-            pos = (pos + 1) & a.mask;
-            const unsigned long long prev = atomicCAS(&a.slots[pos], kEmptySlot, mine);
-            if (prev == kEmptySlot) { pos |= 0x80000000u; break; }
-            if (static_cast<uint32_t>(prev >> 32) == key) { a.shared[pos] = 1; break; }
-        }
+    const uint32_t R = static_cast<uint32_t>(a.K + 2);
+    uint32_t t[kPrepUnroll], key[kPrepUnroll], pos[kPrepUnroll];
+    unsigned long long owner[kPrepUnroll];
+#pragma unroll
+    for (int u = 0; u < kPrepUnroll; ++u) {
+        t[u] = (block * kPrepUnroll + u) * 256u + threadIdx.x;
+        key[u] = 0;
+        if (t[u] < a.refs) key[u] = static_cast<uint32_t>(a.ids[t[u]]) | ((t[u] % R) == 0 ? 0u : 0x80000000u);
     }
-    a.posbuf[t] = pos;
+#pragma unroll
+    for (int u = 0; u < kPrepUnroll; ++u) {
+        pos[u] = hash_key(key[u], a.mask);
+        owner[u] = (t[u] < a.refs) ? a.slots[pos[u]] : 0ull;
+    }
+#pragma unroll
+    for (int u = 0; u < kPrepUnroll; ++u) {
+        if (t[u] >= a.refs) continue;
+        uint32_t p = pos[u];
+        if (static_cast<uint32_t>(owner[u] >> 32) == key[u]) {
+            // my row owns its home position; any reference but the one whose store landed last
+            // proves that the row is named at least twice
+            if (static_cast<uint32_t>(owner[u]) != t[u]) a.shared[p] = 1;
+        } else {
+            // another row owns the home position: probe onwards.  Positions only ever go from empty
+            // to occupied here, and the table holds at most cap/4 keys, so the walk ends.
+            const unsigned long long mine = (static_cast<unsigned long long>(key[u]) << 32) | t[u];
+            while (true) {
+                p = (p + 1) & a.mask;
+                const unsigned long long prev = atomicCAS(&a.slots[p], kEmptySlot, mine);
+                if (prev == kEmptySlot) break;
+                if (static_cast<uint32_t>(prev >> 32) == key[u]) { a.shared[p] = 1; break; }
+            }
+        }
+        a.posbuf[t[u]] = p;
+    }
 }
+
+// Number of blocks either phase needs for `refs` references.
+inline unsigned prep_blocks(uint32_t refs) { return (refs + 256u * kPrepUnroll - 1u) / (256u * kPrepUnroll); }
+
+// Placement of `extra` helper blocks among `total` blocks of a fused launch: every period-th block is
+// a helper until they run out, so helpers and main blocks are resident together from the start.
+__device__ __forceinline__ bool fused_block(unsigned extra, unsigned period, unsigned* index)
+{
+    const unsigned i = blockIdx.x;
+    if (extra && i % period == 0 && i / period < extra) { *index = i / period; return true; }
+    const unsigned before = extra ? min(extra, (i + period - 1) / period) : 0u;
+    *index = i - before;
+    return false;
+}
+
+__global__ __launch_bounds__(256) void claim_kernel(PrepArgs a) { claim_refs(a, blockIdx.x); }
+__global__ __launch_bounds__(256) void resolve_kernel(PrepArgs a) { resolve_refs(a, blockIdx.x); }
 
 // ---------------------------------------------------------------------------------------------
 // train kernel.  G lanes per pair, NCH float4 chunks per lane (chunk index = lg + i*G, valid while
@@ -314,13 +366,19 @@ __device__ __forceinline__ void to_consecutive(const float4 (&v)[NCH], float (&o
 }
 
 template <int G, int NCH, int JB>
-__global__ __launch_bounds__(256) void train_kernel(TrainArgs a)
+__global__ __launch_bounds__(256) void train_kernel(TrainArgs a, PrepArgs next, unsigned claim_blocks, unsigned period)
 {
     constexpr int GROUPS = 256 / G;
     __shared__ float lds[GROUPS][4 * G * NCH];
+    // some blocks do the id-only claim phase of the next batch
+    unsigned block;
+    if (fused_block(claim_blocks, period, &block)) {
+        claim_refs(next, block);
+        return;
+    }
     const int lg = threadIdx.x & (G - 1);
     const int grp = threadIdx.x / G;
-    const int64_t b = static_cast<int64_t>(blockIdx.x) * GROUPS + grp;
+    const int64_t b = static_cast<int64_t>(block) * GROUPS + grp;
     if (b >= a.B) return;   // whole groups leave together; groups never communicate below
     const int K = a.K;
     const int R = K + 2;
@@ -333,7 +391,7 @@ __global__ __launch_bounds__(256) void train_kernel(TrainArgs a)
     int shared_mine = 0;
     if (lg < R) {
         id_mine = a.ids[b * R + lg];
-        pos_mine = a.posbuf[b * R + lg] & kPosMask;
+        pos_mine = a.posbuf[b * R + lg];
         shared_mine = a.shared[pos_mine];
     }
 
@@ -426,50 +484,57 @@ __global__ __launch_bounds__(256) void train_kernel(TrainArgs a)
 }
 
 // ---------------------------------------------------------------------------------------------
-// apply kernel: one thread per row reference.  The reference that owns a hash position empties it;
-// the block then collects the shared rows among its positions in LDS and 16-lane groups add each
-// row's slot to the table row and zero the slot.
+// apply kernel.  Two kinds of blocks:
+//   resolve_blocks of them (spread over the grid): resolve phase of the next batch (other set of
+//                         hash state)
+//   the rest              sweep the batch's hash positions in order, 8 per thread: read the shared
+//                         flags, empty the positions and clear the flags with full-width stores
+//                         (a linear pass is far cheaper than one partial store per reference), collect
+//                         the shared rows in LDS, then 16-lane groups add each row's slot to the
+//                         table row and zero the slot.
 // ---------------------------------------------------------------------------------------------
+constexpr int kSweepPerThread = 8;
+constexpr int kSweepPerBlock = 256 * kSweepPerThread;
+
 struct ApplyArgs {
     float4* X;
     float4* C;
     int32_t d4;
     float4* delta;
-    int64_t refs;
-    int32_t R;
-    const int32_t* ids;
-    const uint32_t* posbuf;
+    uint32_t positions;   // hash positions in use for this batch (a power of two, multiple of 2048)
     unsigned long long* slots;
     uint8_t* shared;
 };
 
-__global__ __launch_bounds__(256) void apply_kernel(ApplyArgs a)
+__global__ __launch_bounds__(256) void apply_kernel(ApplyArgs a, PrepArgs next, unsigned resolve_blocks,
+                                                    unsigned period)
 {
-    __shared__ uint2 todo_list[256];   // (position, key) of the shared rows this block applies
+    __shared__ uint2 todo_list[kSweepPerBlock];   // (position, key) of the shared rows of this block's span
     __shared__ int todo_count;
+    unsigned block;
+    if (fused_block(resolve_blocks, period, &block)) {
+        resolve_refs(next, block);
+        return;
+    }
     if (threadIdx.x == 0) todo_count = 0;
     __syncthreads();
-    const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    bool todo = false;
-    uint32_t pos = 0, key = 0;
-    if (t < a.refs) {
-        const uint32_t p = a.posbuf[t];
-        if (p & 0x80000000u) {
-            pos = p & kPosMask;
-            todo = a.shared[pos] != 0;
-            if (todo) a.shared[pos] = 0;
-            a.slots[pos] = kEmptySlot;
-            if (todo) key = static_cast<uint32_t>(a.ids[t]) | ((t % a.R) != 0 ? 0x80000000u : 0u);
+    const uint32_t first = block * kSweepPerBlock + threadIdx.x * kSweepPerThread;
+    const uint64_t flags = *reinterpret_cast<const uint64_t*>(a.shared + first);
+    if (flags) {
+        *reinterpret_cast<uint64_t*>(a.shared + first) = 0ull;
+#pragma unroll
+        for (int i = 0; i < kSweepPerThread; ++i) {
+            if ((flags >> (8 * i)) & 0xFFull) {
+                const uint32_t key = static_cast<uint32_t>(a.slots[first + i] >> 32);
+                todo_list[atomicAdd(&todo_count, 1)] = make_uint2(first + i, key);
+            }
         }
     }
-    const uint64_t votes = __ballot(todo);
-    if (votes) {
-        const int lane = threadIdx.x & 63;
-        const int leader = __ffsll(static_cast<long long>(votes)) - 1;
-        int base = 0;
-        if (lane == leader) base = atomicAdd(&todo_count, static_cast<int>(__popcll(votes)));
-        base = __shfl(base, leader, 64);
-        if (todo) todo_list[base + static_cast<int>(__popcll(votes & ((1ull << lane) - 1ull)))] = make_uint2(pos, key);
+    {
+        ulonglong2* out = reinterpret_cast<ulonglong2*>(a.slots + first);
+        const ulonglong2 empty2 = make_ulonglong2(kEmptySlot, kEmptySlot);
+#pragma unroll
+        for (int i = 0; i < kSweepPerThread / 2; ++i) out[i] = empty2;
     }
     __syncthreads();
     const int n = todo_count;
@@ -606,13 +671,15 @@ bool pick_shape(int32_t d4, int32_t K, Shape* out)
 
 #define NE_FOR_EACH_SHAPE(M) M(8, 1) M(16, 1) M(16, 2) M(32, 1) M(32, 2) M(64, 1) M(64, 2) M(64, 4)
 
-hipError_t launch_train(const Shape& s, const TrainArgs& a, hipStream_t st)
+hipError_t launch_train(const Shape& s, const TrainArgs& a, const PrepArgs& next, hipStream_t st)
 {
     const int groups = 256 / s.G;
-    const unsigned grid = static_cast<unsigned>((a.B + groups - 1) / groups);
+    const unsigned claim_blocks = prep_blocks(next.refs);
+    const unsigned grid = claim_blocks + static_cast<unsigned>((a.B + groups - 1) / groups);
+    const unsigned period = claim_blocks ? grid / claim_blocks : 1u;
 #define NE_CASE(G_, N_)                                                                          \
     if (s.G == G_ && s.NCH == N_) {                                                              \
-        hipLaunchKernelGGL((train_kernel<G_, N_, 6>), dim3(grid), dim3(256), 0, st, a);          \
+        hipLaunchKernelGGL((train_kernel<G_, N_, 6>), dim3(grid), dim3(256), 0, st, a, next, claim_blocks, period); \
         return hipGetLastError();                                                                \
     }
     NE_FOR_EACH_SHAPE(NE_CASE)
@@ -645,7 +712,7 @@ bool workspace_layout(int32_t dim, int64_t max_B, int32_t max_K, char* base, Wor
         max_K > NE_MAX_NEGATIVES)
         return false;
     const uint64_t refs = static_cast<uint64_t>(max_B) * (max_K + 2);
-    uint64_t cap = 1024;
+    uint64_t cap = 2048;   // one sweep block of the apply kernel
     while (cap < 4 * refs) cap <<= 1;
     auto up = [](size_t v) { return (v + 255) & ~static_cast<size_t>(255); };
     size_t off = 0;
@@ -720,7 +787,6 @@ ne_status ne_create_tables(ne_tables** out, int64_t num_nodes, int32_t dim, floa
     if (!t) return fail(NE_ERR_NOMEM, "host allocation failed");
     t->num_nodes = num_nodes; t->dim = dim; t->vertex = vertex_dev; t->context = context_dev; t->seed = seed;
     t->max_batch = 0; t->max_negatives = 0; t->batches_done = 0; t->profile_every = 0; t->ev_used = 0;
-    t->prepared[0] = {0, 0, false}; t->prepared[1] = {0, 0, false};
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
 
     if (workspace_dev || max_batch > 0) {   // training requested
@@ -871,89 +937,96 @@ ne_status ne_build_neg_alias(ne_alias** out, const uint32_t* degree_host, int64_
     return NE_OK;
 }
 
-ne_status ne_prepare_batch(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t B, int32_t K,
-                           uint64_t sample_base, int32_t* neg_out_dev, int32_t slot, void* hip_stream)
+ne_status ne_train_block(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t n_pairs, int64_t B,
+                         int32_t K, const float* lr_host, uint64_t sample_base, int32_t* neg_out_dev,
+                         void* hip_stream)
 {
     Shape shape;
     ne_status rc = check_batch_args(t, al, pairs_dev, B, K, &shape);
     if (rc != NE_OK) return rc;
-    if (slot < 0 || slot > 1) return fail(NE_ERR_ARG, "slot must be 0 or 1");
+    if (n_pairs < 0 || n_pairs > (static_cast<int64_t>(1) << 40)) return fail(NE_ERR_ARG, "n_pairs out of range");
+    if (n_pairs == 0) return NE_OK;
+    if (B < 1) return fail(NE_ERR_ARG, "B must be at least 1");
+    if (!lr_host) return fail(NE_ERR_ARG, "lr_host is NULL");
+    const int64_t n_batches = (n_pairs + B - 1) / B;
+    for (int64_t i = 0; i < n_batches; ++i)
+        if (!std::isfinite(lr_host[i])) return fail(NE_ERR_ARG, "lr is not finite");
     if (t->max_batch <= 0) return fail(NE_ERR_STATE, "tables were created without a training workspace");
     if (B > t->max_batch || K > t->max_negatives)
         return fail(NE_ERR_ARG, "B or K exceeds the max_batch / max_negatives the workspace was sized for");
-    if (t->prepared[slot].ready) return fail(NE_ERR_STATE, "slot holds a prepared batch that was not trained yet");
-    t->prepared[slot] = {B, K, true};
-    if (B == 0) return NE_OK;
 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const Workspace& w = t->ws;
-    const PrepSlot& ps = w.prep[slot];
-    PrepArgs pa{};
-    pa.pairs = reinterpret_cast<const int2*>(pairs_dev);
-    pa.B = B; pa.K = K; pa.sample_base = sample_base;
-    pa.k0 = static_cast<uint32_t>(t->seed); pa.k1 = static_cast<uint32_t>(t->seed >> 32);
-    pa.alias = al ? al->table : nullptr; pa.alias_n = al ? static_cast<uint64_t>(al->n) : 1; pa.alias_base = al ? al->base : 0;
-    pa.slots = ps.slots; pa.mask = w.cap - 1; pa.shared = ps.shared; pa.ids = ps.ids; pa.posbuf = ps.posbuf;
-    pa.neg_out = neg_out_dev;
-    const unsigned grid = static_cast<unsigned>((B * (K + 2) + 255) / 256);
-    hipLaunchKernelGGL(claim_kernel, dim3(grid), dim3(256), 0, st, pa);
+    const int R = K + 2;
+
+    auto prep_args = [&](int64_t i) {
+        PrepArgs pa{};
+        if (i >= n_batches) return pa;   // refs = 0: nothing to prepare
+        const int64_t first = i * B;
+        const int64_t Bi = (n_pairs - first < B) ? n_pairs - first : B;
+        const PrepSlot& ps = w.prep[i & 1];
+        pa.pairs = reinterpret_cast<const int2*>(pairs_dev) + first;
+        pa.refs = static_cast<uint32_t>(Bi * R); pa.K = K; pa.sample_base = sample_base + static_cast<uint64_t>(first);
+        pa.k0 = static_cast<uint32_t>(t->seed); pa.k1 = static_cast<uint32_t>(t->seed >> 32);
+        pa.alias = al ? al->table : nullptr; pa.alias_n = al ? static_cast<uint64_t>(al->n) : 1; pa.alias_base = al ? al->base : 0;
+        uint32_t positions = kSweepPerBlock;     // hash positions this batch uses: >= 4 * references
+        while (positions < 4u * static_cast<uint32_t>(Bi * R)) positions <<= 1;
+        pa.slots = ps.slots; pa.mask = positions - 1; pa.shared = ps.shared; pa.ids = ps.ids; pa.posbuf = ps.posbuf;
+        pa.neg_out = neg_out_dev ? neg_out_dev + first * K : nullptr;
+        return pa;
+    };
+
+    // the first batch has no predecessor to ride along with
+    PrepArgs cur = prep_args(0);
+    const unsigned grid0 = prep_blocks(cur.refs);
+    hipLaunchKernelGGL(claim_kernel, dim3(grid0), dim3(256), 0, st, cur);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("claim launch: ") + hipGetErrorString(e));
-    hipLaunchKernelGGL(resolve_kernel, dim3(grid), dim3(256), 0, st, pa);
+    hipLaunchKernelGGL(resolve_kernel, dim3(grid0), dim3(256), 0, st, cur);
     e = hipGetLastError();
     if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("resolve launch: ") + hipGetErrorString(e));
-    return NE_OK;
-}
 
-ne_status ne_train_prepared(ne_tables* t, int32_t slot, float lr, void* hip_stream)
-{
-    if (!t) return fail(NE_ERR_ARG, "tables handle is NULL");
-    if (slot < 0 || slot > 1) return fail(NE_ERR_ARG, "slot must be 0 or 1");
-    if (!std::isfinite(lr)) return fail(NE_ERR_ARG, "lr is not finite");
-    if (!t->prepared[slot].ready) return fail(NE_ERR_STATE, "no prepared batch in this slot");
-    const int64_t B = t->prepared[slot].B;
-    const int32_t K = t->prepared[slot].K;
-    t->prepared[slot].ready = false;
-    if (B == 0) return NE_OK;
-    Shape shape;
-    if (!pick_shape(t->dim / 4, K, &shape)) return fail(NE_ERR_ARG, "no launch shape for this (dim, K)");
+    for (int64_t i = 0; i < n_batches; ++i) {
+        const PrepArgs next = prep_args(i + 1);
+        const PrepSlot& ps = w.prep[i & 1];
+        TrainArgs ta{};
+        ta.X = reinterpret_cast<float4*>(t->vertex); ta.C = reinterpret_cast<float4*>(t->context);
+        ta.B = cur.refs / R; ta.K = K; ta.d4 = t->dim / 4; ta.lr = lr_host[i];
+        ta.ids = ps.ids; ta.posbuf = ps.posbuf; ta.shared = ps.shared; ta.delta = w.delta;
+        const bool timed = t->profile_every > 0 && t->batches_done % static_cast<uint64_t>(t->profile_every) == 0 &&
+                           t->ev_used < t->ev_start.size();
+        if (timed) NE_HIP_CHECK(hipEventRecord(t->ev_start[t->ev_used], st));
+        e = launch_train(shape, ta, next, st);
+        if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("train launch: ") + hipGetErrorString(e));
+        if (timed) {
+            NE_HIP_CHECK(hipEventRecord(t->ev_stop[t->ev_used], st));
+            t->ev_used += 1;
+        }
 
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const Workspace& w = t->ws;
-    const PrepSlot& ps = w.prep[slot];
-    TrainArgs ta{};
-    ta.X = reinterpret_cast<float4*>(t->vertex); ta.C = reinterpret_cast<float4*>(t->context);
-    ta.B = B; ta.K = K; ta.d4 = t->dim / 4; ta.lr = lr;
-    ta.ids = ps.ids; ta.posbuf = ps.posbuf; ta.shared = ps.shared; ta.delta = w.delta;
-    const bool timed = t->profile_every > 0 && t->batches_done % static_cast<uint64_t>(t->profile_every) == 0 &&
-                       t->ev_used < t->ev_start.size();
-    if (timed) NE_HIP_CHECK(hipEventRecord(t->ev_start[t->ev_used], st));
-    hipError_t e = launch_train(shape, ta, st);
-    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("train launch: ") + hipGetErrorString(e));
-    if (timed) {
-        NE_HIP_CHECK(hipEventRecord(t->ev_stop[t->ev_used], st));
-        t->ev_used += 1;
+        ApplyArgs aa{};
+        aa.X = ta.X; aa.C = ta.C; aa.d4 = ta.d4; aa.delta = reinterpret_cast<float4*>(w.delta);
+        aa.positions = cur.mask + 1; aa.slots = ps.slots; aa.shared = ps.shared;
+        const unsigned resolve_blocks = prep_blocks(next.refs);
+        const unsigned sweep_blocks = aa.positions / kSweepPerBlock;
+        const unsigned apply_grid = resolve_blocks + sweep_blocks;
+        hipLaunchKernelGGL(apply_kernel, dim3(apply_grid), dim3(256), 0, st, aa, next, resolve_blocks,
+                           resolve_blocks ? apply_grid / resolve_blocks : 1u);
+        e = hipGetLastError();
+        if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("apply launch: ") + hipGetErrorString(e));
+        t->batches_done += 1;
+        cur = next;
     }
-
-    ApplyArgs aa{};
-    aa.X = ta.X; aa.C = ta.C; aa.d4 = ta.d4; aa.delta = reinterpret_cast<float4*>(w.delta);
-    aa.refs = B * (K + 2); aa.R = K + 2; aa.ids = ps.ids; aa.posbuf = ps.posbuf; aa.slots = ps.slots; aa.shared = ps.shared;
-    hipLaunchKernelGGL(apply_kernel, dim3(static_cast<unsigned>((aa.refs + 255) / 256)), dim3(256), 0, st, aa);
-    e = hipGetLastError();
-    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("apply launch: ") + hipGetErrorString(e));
-    t->batches_done += 1;
     return NE_OK;
 }
 
 ne_status ne_train_batch(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t B, int32_t K,
                          float lr, uint64_t sample_base, int32_t* neg_out_dev, void* hip_stream)
 {
-    if (!std::isfinite(lr)) return fail(NE_ERR_ARG, "lr is not finite");
-    if (t && (t->prepared[0].ready || t->prepared[1].ready))
-        return fail(NE_ERR_STATE, "a batch prepared with ne_prepare_batch is still pending");
-    ne_status rc = ne_prepare_batch(t, al, pairs_dev, B, K, sample_base, neg_out_dev, 0, hip_stream);
-    if (rc != NE_OK) return rc;
-    return ne_train_prepared(t, 0, lr, hip_stream);
+    if (B == 0) {
+        Shape shape;
+        return check_batch_args(t, al, pairs_dev, B, K, &shape);
+    }
+    return ne_train_block(t, al, pairs_dev, B, B, K, &lr, sample_base, neg_out_dev, hip_stream);
 }
 
 ne_status ne_eval_loss(const ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t B, int32_t K,

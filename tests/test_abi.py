@@ -63,6 +63,12 @@ def test_host_side_argument_errors():
     assert L.ne_train_batch(tables, None, fake, 1, 0, float("nan"), 0, None, None) == ne.NE_ERR_ARG
     assert L.ne_train_batch(tables, None, fake, 1, 0, 0.1, 0, None, None) == ne.NE_ERR_STATE    # no workspace
     assert b"workspace" in L.ne_last_error()
+    lr = (ctypes.c_float * 2)(0.1, 0.1)
+    assert L.ne_train_block(tables, None, fake, 10, 0, 0, lr, 0, None, None) == ne.NE_ERR_ARG       # B = 0
+    assert L.ne_train_block(tables, None, fake, -5, 8, 0, lr, 0, None, None) == ne.NE_ERR_ARG
+    assert L.ne_train_block(tables, None, fake, 10, 8, 0, None, 0, None, None) == ne.NE_ERR_ARG     # no lr
+    assert L.ne_train_block(tables, None, fake, 10, 8, 0, lr, 0, None, None) == ne.NE_ERR_STATE     # no workspace
+    assert L.ne_train_block(tables, None, fake, 0, 8, 0, lr, 0, None, None) == ne.NE_OK             # nothing to do
     assert L.ne_eval_loss(tables, None, fake, 1, 0, 0, None, None, None) == ne.NE_ERR_ARG
     assert L.ne_eval_loss(tables, None, fake, 0, 0, 0, fake, None, None) == ne.NE_OK            # B = 0
     assert L.ne_build_neg_alias(ctypes.byref(out), None, 4, 0, fake, None) == ne.NE_ERR_ARG

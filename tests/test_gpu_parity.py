@@ -196,52 +196,49 @@ def test_empty_batch_and_validate():
         ne.ne_train_batch(m.tables, a2, pairs[:1], K, 0.1, 0)
 
 
-def test_two_stream_pipeline_matches_oracle():
-    """ne_prepare_batch of batch t+1 on a second stream while batch t trains (two slots)."""
-    say("two-stream pipeline")
-    V, d, K, B, seed, nb = 6000, 128, 5, 2048, 3, 12
+def test_train_block_matches_oracle_and_single_batches():
+    """ne_train_block (claim/resolve of batch i+1 fused into the kernels of batch i) on a run of
+    batches with a ragged tail: equals the oracle, and equals ne_train_batch called per batch."""
+    say("train_block")
+    V, d, K, B, seed = 6000, 128, 5, 2048, 3
+    n_pairs = 11 * B + 777
+    nb = -(-n_pairs // B)
     rng = np.random.default_rng(1)
     deg = (rng.pareto(1.0, V) * 2).astype(np.uint32) + 1
-    m = GpuModel(V, d, seed, deg, K, B)
-    Xo, Co = oracle.init_tables(V, d, seed)
-    Xo[:] = rng.normal(0, 0.2, Xo.shape).astype(np.float32)
-    Co[:] = rng.normal(0, 0.2, Co.shape).astype(np.float32)
-    m.vertex.copy_(torch.from_numpy(Xo)); m.context.copy_(torch.from_numpy(Co))
-    thr, alias, _ = oracle.build_alias(deg)
-    ids = np.minimum((rng.pareto(0.8, (nb, B, 2)) * V / 50).astype(np.int64), V - 1).astype(np.int32)
+    X0 = rng.normal(0, 0.2, (V, d)).astype(np.float32)
+    C0 = rng.normal(0, 0.2, (V, d)).astype(np.float32)
+    ids = np.minimum((rng.pareto(0.8, (n_pairs, 2)) * V / 50).astype(np.int64), V - 1).astype(np.int32)
+    lrs = [wl.linear_decay_lr(0.05, i * B, n_pairs) for i in range(nb)]
     pairs_dev = torch.from_numpy(ids).cuda()
-    negs = [torch.empty((B, K), dtype=torch.int32, device="cuda:0") for _ in range(nb)]
-    torch.cuda.synchronize()
-    s_prep, s_train = torch.cuda.Stream(), torch.cuda.Stream()
-    prepared = [torch.cuda.Event() for _ in range(nb)]
-    trained = [torch.cuda.Event() for _ in range(nb)]
-    for t in range(nb + 1):
-        if t < nb:
-            if t >= 2:
-                s_prep.wait_event(trained[t - 2])        # the slot is free again
-            ne.ne_prepare_batch(m.tables, m.alias, pairs_dev[t], K, t * B, t & 1, negs[t], stream=s_prep)
-            prepared[t].record(s_prep)
-        if t >= 1:
-            u = t - 1
-            s_train.wait_event(prepared[u])
-            ne.ne_train_prepared(m.tables, u & 1, 0.05, stream=s_train)
-            trained[u].record(s_train)
-    torch.cuda.synchronize()
-    for t in range(nb):
-        neg_o = oracle.sample_negatives(seed, t * B, B, K, thr, alias)
-        assert np.array_equal(negs[t].cpu().numpy(), neg_o)
-        oracle.train_batch(Xo, Co, ids[t], neg_o, 0.05)
+    base = 2**33 + 11
+
+    m = GpuModel(V, d, seed, deg, K, B, X=X0, C=C0)
+    negs = torch.empty((n_pairs, K), dtype=torch.int32, device="cuda:0")
+    ne.ne_train_block(m.tables, m.alias, pairs_dev, B, K, lrs, base, negs)
     Xg, Cg = m.host_tables()
+
+    thr, alias, _ = oracle.build_alias(deg)
+    Xo, Co = X0.copy(), C0.copy()
+    neg_all = oracle.sample_negatives(seed, base, n_pairs, K, thr, alias)
+    assert np.array_equal(negs.cpu().numpy(), neg_all)
+    for i in range(nb):
+        sl = slice(i * B, min((i + 1) * B, n_pairs))
+        oracle.train_batch(Xo, Co, np.ascontiguousarray(ids[sl]), np.ascontiguousarray(neg_all[sl]), lrs[i])
     ex, ec = rowwise_rel_err(Xg, Xo), rowwise_rel_err(Cg, Co)
-    say(f"  rowwise err X {ex:.2e} C {ec:.2e}")
+    say(f"  block vs oracle: rowwise err X {ex:.2e} C {ec:.2e}")
     assert ex <= 1e-3 and ec <= 1e-3
-    # slot protocol errors are reported, not executed
-    with pytest.raises(ne.NeError):
-        ne.ne_train_prepared(m.tables, 0, 0.05)
-    ne.ne_prepare_batch(m.tables, m.alias, pairs_dev[0], K, 0, 1)
-    with pytest.raises(ne.NeError):
-        ne.ne_prepare_batch(m.tables, m.alias, pairs_dev[0], K, 0, 1)
-    with pytest.raises(ne.NeError):
-        ne.ne_train_batch(m.tables, m.alias, pairs_dev[0], K, 0.05, 0)
-    ne.ne_train_prepared(m.tables, 1, 0.0)
-    torch.cuda.synchronize()
+
+    m2 = GpuModel(V, d, seed, deg, K, B, X=X0, C=C0)
+    for i in range(nb):
+        sl = slice(i * B, min((i + 1) * B, n_pairs))
+        ne.ne_train_batch(m2.tables, m2.alias, pairs_dev[sl], K, lrs[i], base + i * B)
+    X2, C2 = m2.host_tables()
+    assert rowwise_rel_err(Xg, X2) <= 1e-4 and rowwise_rel_err(Cg, C2) <= 1e-4
+    # a second block on the same handle starts from clean hash state
+    ne.ne_train_block(m.tables, m.alias, pairs_dev[:3 * B + 5], B, K, lrs[:4], 0)
+    for i in range(4):
+        sl = slice(i * B, min((i + 1) * B, 3 * B + 5))
+        neg_o = oracle.sample_negatives(seed, i * B, sl.stop - sl.start, K, thr, alias)
+        oracle.train_batch(Xo, Co, np.ascontiguousarray(ids[sl]), neg_o, lrs[i])
+    Xg, Cg = m.host_tables()
+    assert rowwise_rel_err(Xg, Xo) <= 1e-3 and rowwise_rel_err(Cg, Co) <= 1e-3
