@@ -36,7 +36,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per train-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see
 # profiles/), scaled by the factor a plain copy kernel of known size reads on the same counters.
 # None = not measured for that workload.
-TRAFFIC_BYTES_PER_LAUNCH = {"c1": None, "c2": None, "c3": None, "c4": None}
+TRAFFIC_BYTES_PER_LAUNCH = {"c1": None, "c2": None, "c3": 564.2e6, "c4": None}
 
 WORKLOADS = {
     "c1": dict(V=10_000, edges=100_000, d=128, K=5, B=4096, grid=1, abc=(0.57, 0.19, 0.19), walk=(40, 5), seed=0),
@@ -91,6 +91,8 @@ def main():
     ap.add_argument("--per-batch", action="store_true", help="one library call per batch (no fused prepare)")
     ap.add_argument("--cpu-batches", type=int, default=0, help="oracle batches to time (0 = auto)")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (experiments)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run 20 plain 1 GiB device copies (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -101,6 +103,14 @@ def main():
         sys.exit(1)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(20):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": 20}}))
+        return
     name = args.workload
     if args.batch > 0:
         WORKLOADS[name] = dict(WORKLOADS[name], B=args.batch)
