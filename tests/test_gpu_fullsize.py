@@ -1,0 +1,149 @@
+"""Parity at the benchmark's full sizes and launch configuration (ne_train_block, batch 65536).
+
+Config 2 (1 M nodes): the oracle runs the same batches on host copies of the tables; every element is
+compared.  Config 3 (100 M nodes, 102 GB of tables): host copies are impossible, so sampled table rows
+are checked one by one: for a sample of touched rows, every pair of the batch that names one of them
+is collected, the pre-batch values of all rows those pairs read are fetched, and the oracle runs on
+that sub-batch (ids renumbered); its result for the sampled rows is exact because a row's update
+depends only on the pairs that name it.  Plus properties that hold at any size: negatives bit-exact and
+inside the context block, rows no pair names bit-identical.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2005_13789_amd as ne
+import workloads as wl
+from parity_util import rowwise_rel_err
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def make_tables(V, d, K, B, seed):
+    vertex = torch.empty((V, d), dtype=torch.float32, device=DEV)
+    context = torch.empty((V, d), dtype=torch.float32, device=DEV)
+    ws = torch.empty(ne.ne_workspace_bytes(d, B, K), dtype=torch.uint8, device=DEV)
+    t = ne.ne_create_tables(vertex, context, seed, init=True, max_batch=B, max_negatives=K, workspace=ws)
+    return t
+
+
+def test_config2_full_compare():
+    say("config 2: 1M nodes, 20M edges, walks of 80, window 5, B=65536; 3 batches, every element")
+    V, d, K, B, seed, nb = 1_000_000, 128, 5, 65536, 1, 3
+    g = wl.build_graph(V, wl.rmat_edges(V, 20_000_000, seed, device=DEV))
+    pairs = wl.walk_pairs(g, 80, 5, nb * B, seed)
+    deg = g.degree.cpu().numpy().astype(np.uint32)
+    del g
+    t = make_tables(V, d, K, B, seed)
+    at = torch.empty((V, 2), dtype=torch.int32, device=DEV)
+    alias = ne.ne_build_neg_alias(deg, 0, at)
+    # two warm-up batches so that the compared batches start from non-trivial tables
+    lrs = [0.025, 0.02, 0.015]
+    neg = torch.empty((nb * B, K), dtype=torch.int32, device=DEV)
+    X0 = None
+    ne.ne_train_block(t, alias, pairs[:B], B, K, lrs[:1], 0, neg[:B])
+    torch.cuda.synchronize()
+    Xo, Co = t.vertex.cpu().numpy(), t.context.cpu().numpy()
+    ne.ne_train_block(t, alias, pairs[B:], B, K, lrs[1:], B, neg[B:])
+    torch.cuda.synchronize()
+    thr, al, _ = oracle.build_alias(deg)
+    pn = pairs.cpu().numpy()
+    neg_all = oracle.sample_negatives(seed, 0, nb * B, K, thr, al)
+    assert np.array_equal(neg.cpu().numpy(), neg_all)
+    Xpre, Cpre = Xo.copy(), Co.copy()
+    for i in (1, 2):
+        sl = slice(i * B, (i + 1) * B)
+        oracle.train_batch(Xo, Co, np.ascontiguousarray(pn[sl]), np.ascontiguousarray(neg_all[sl]), lrs[i])
+    Xg, Cg = t.vertex.cpu().numpy(), t.context.cpu().numpy()
+    ex, ec = rowwise_rel_err(Xg, Xo), rowwise_rel_err(Cg, Co)
+    say(f"  rowwise err X {ex:.2e} C {ec:.2e}")
+    assert ex <= 1e-4 and ec <= 1e-4       # two batches from a common starting point
+    touched_x = np.zeros(V, bool); touched_x[pn[B:, 0]] = True
+    touched_c = np.zeros(V, bool); touched_c[pn[B:, 1]] = True; touched_c[neg_all[B:].reshape(-1)] = True
+    assert np.array_equal(Xg[~touched_x].view(np.uint32), Xpre[~touched_x].view(np.uint32))
+    assert np.array_equal(Cg[~touched_c].view(np.uint32), Cpre[~touched_c].view(np.uint32))
+
+
+def sampled_row_check(t, alias, pairs_dev, K, lr, sample_base, n_sample, rng):
+    """Train one batch with ne_train_block and check n_sample touched rows of each table."""
+    B = pairs_dev.shape[0]
+    d = t.dim
+    neg = torch.empty((B, K), dtype=torch.int32, device=DEV)
+    loss = torch.zeros((), dtype=torch.float64, device=DEV)
+    ne.ne_eval_loss(t, alias, pairs_dev, K, sample_base, loss, neg)      # same draws as training
+    torch.cuda.synchronize()
+    p = pairs_dev.long()
+    cref = torch.cat([p[:, 1:2], neg.long()], dim=1)                     # [B][K+1] context rows per pair
+    # sample: a mix of rows named once and rows named often
+    cu, cc = torch.unique(cref.reshape(-1), return_counts=True)
+    xu, xc = torch.unique(p[:, 0], return_counts=True)
+    def pick(u, c):
+        hot = u[torch.argsort(c, descending=True)[: n_sample // 4]]
+        rest = u[torch.from_numpy(rng.choice(u.numel(), n_sample - hot.numel(), replace=False)).to(DEV)]
+        return torch.unique(torch.cat([hot, rest]))
+    srows_c, srows_x = pick(cu, cc), pick(xu, xc)
+    sel = torch.isin(p[:, 0], srows_x) | torch.isin(cref, srows_c).any(dim=1)
+    sub_pairs, sub_neg = p[sel], neg.long()[sel]
+    say(f"  {int(sel.sum())} pairs name one of {srows_x.numel()} + {srows_c.numel()} sampled rows")
+    # renumber the rows the sub-batch reads and fetch their pre-batch values
+    xs, xinv = torch.unique(sub_pairs[:, 0], return_inverse=True)
+    cs, cinv = torch.unique(torch.cat([sub_pairs[:, 1:2], sub_neg], dim=1), return_inverse=True)
+    n = max(xs.numel(), cs.numel())
+    Xm = np.zeros((n, d), np.float32); Cm = np.zeros((n, d), np.float32)
+    Xm[: xs.numel()] = t.vertex[xs].cpu().numpy()
+    Cm[: cs.numel()] = t.context[cs].cpu().numpy()
+    mp = np.stack([xinv.cpu().numpy(), cinv[:, 0].cpu().numpy()], axis=1).astype(np.int32)
+    mn = np.ascontiguousarray(cinv[:, 1:].cpu().numpy().astype(np.int32))
+    # untouched sample for the bit-identical check
+    probe = torch.from_numpy(rng.integers(0, t.num_nodes, 4096)).to(DEV)
+    probe_c = probe[~torch.isin(probe, cu)]
+    probe_x = probe[~torch.isin(probe, xu)]
+    before_c, before_x = t.context[probe_c].clone(), t.vertex[probe_x].clone()
+
+    negs_train = torch.empty_like(neg)
+    ne.ne_train_block(t, alias, pairs_dev, B, K, [lr], sample_base, negs_train)
+    torch.cuda.synchronize()
+    assert torch.equal(negs_train, neg)
+    oracle.train_batch(Xm, Cm, mp, mn, lr)
+    gx = t.vertex[srows_x].cpu().numpy()
+    gc = t.context[srows_c].cpu().numpy()
+    ox = Xm[torch.searchsorted(xs, srows_x).cpu().numpy()]
+    oc = Cm[torch.searchsorted(cs, srows_c).cpu().numpy()]
+    ex, ec = rowwise_rel_err(gx, ox), rowwise_rel_err(gc, oc)
+    say(f"  sampled rows: rowwise err X {ex:.2e} C {ec:.2e}")
+    assert ex <= 1e-4 and ec <= 1e-4
+    assert torch.equal(t.context[probe_c], before_c) and torch.equal(t.vertex[probe_x], before_x)
+    return neg
+
+
+def test_config3_sampled_rows():
+    say("config 3: 100M nodes, d=128, K=5, B=65536, 4x4 buckets, negatives inside the context block")
+    V, d, K, B, seed, grid = 100_000_000, 128, 5, 65536, 2, 4
+    rng = np.random.default_rng(0)
+    degree = wl.rmat_degrees(V, 400_000_000, seed, device=DEV)          # a fifth of the edges: same shape, less set-up
+    pairs = wl.rmat_pairs(V, 80 * B, seed, device=DEV)
+    bp = wl.bucket_pairs(pairs, V, grid)
+    sched = [s for s in wl.orthogonal_schedule(bp, B) if s[1] == B]
+    t = make_tables(V, d, K, B, seed)
+    s0, n0, bi, bj = sched[0]
+    lo, hi = bj * bp.block_rows, min((bj + 1) * bp.block_rows, V)
+    deg_blk = degree[lo:hi].clamp(max=2**32 - 1).cpu().numpy().astype(np.uint32)
+    at = torch.empty((hi - lo, 2), dtype=torch.int32, device=DEV)
+    alias = ne.ne_build_neg_alias(deg_blk, lo, at)
+    # batches of the same bucket: the first from the initial tables, the later ones from trained tables
+    same = [s for s in sched if (s[2], s[3]) == (bi, bj)][:3]
+    assert len(same) >= 2
+    thr, al, _ = oracle.build_alias(deg_blk)
+    for k, (s, n, _, _) in enumerate(same):
+        pd = bp.pairs[s:s + n]
+        assert int((pd[:, 0].long() // bp.block_rows != bi).sum()) == 0
+        neg = sampled_row_check(t, alias, pd, K, 0.025, 1000 * k, 256, rng)
+        assert int(neg.min()) >= lo and int(neg.max()) < hi
+        want = oracle.sample_negatives(seed, 1000 * k, 2048, K, thr, al, lo)
+        assert np.array_equal(neg[:2048].cpu().numpy(), want)
