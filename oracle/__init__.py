@@ -51,6 +51,9 @@ def _load():
     lib.oracle_train_batch.argtypes = [p, p, c.c_int64, c.c_int32, p, c.c_int64, c.c_int32,
                                        c.c_float, p]
     lib.oracle_train_batch.restype = c.c_int
+    lib.oracle_train_batch_shared.argtypes = [p, p, c.c_int64, c.c_int32, p, c.c_int64, p, c.c_int32, c.c_float,
+                                              c.c_float, c.c_int32, c.POINTER(c.c_double)]
+    lib.oracle_train_batch_shared.restype = c.c_int
     lib.oracle_eval_loss.argtypes = [p, p, c.c_int64, c.c_int32, p, c.c_int64, c.c_int32, p]
     lib.oracle_eval_loss.restype = c.c_double
     _lib = lib
@@ -148,3 +151,25 @@ def eval_loss(X: np.ndarray, C: np.ndarray, pairs: np.ndarray, neg: np.ndarray) 
     K = neg.shape[1]
     assert neg.shape == (B, K)
     return float(_load().oracle_eval_loss(_ptr(X), _ptr(C), V, d, _ptr(pairs), B, K, _ptr(neg)))
+
+
+def train_batch_shared(X: np.ndarray, C: np.ndarray, pairs: np.ndarray, negs: np.ndarray, lr: float,
+                       neg_scale: float, bf16_inputs: bool = True) -> float:
+    """Shared-negative step in place on X and C; returns the summed loss at the pre-batch tables.
+
+    Every pair is scored against all N ids of negs (int32[N]); negative terms carry weight neg_scale.
+    bf16_inputs rounds the rows and the coefficients of the dense products to bfloat16 first.
+    """
+    _chk(X, np.float32, "X")
+    _chk(C, np.float32, "C")
+    _chk(pairs, np.int32, "pairs")
+    _chk(negs, np.int32, "negs")
+    V, d = X.shape
+    B = pairs.shape[0]
+    loss = ctypes.c_double()
+    rc = _load().oracle_train_batch_shared(_ptr(X), _ptr(C), V, d, _ptr(pairs), B, _ptr(negs), negs.shape[0],
+                                           np.float32(lr), np.float32(neg_scale), 1 if bf16_inputs else 0,
+                                           ctypes.byref(loss))
+    if rc != 0:
+        raise ValueError(f"oracle_train_batch_shared failed ({rc})")
+    return loss.value

@@ -286,3 +286,93 @@ double oracle_eval_loss(const float* X, const float* C, int64_t V, int32_t d, co
     }
     return total;
 }
+
+/* ------------------------------------------------------------------------- */
+/* Shared-negative mode (the level-3-BLAS formulation the paper cites as       */
+/* related work, Sec. VI-B: the negatives are shared by a whole mini-batch so  */
+/* that scoring becomes a dense product).  All B pairs of the batch are scored */
+/* against the same N negative rows; every negative term carries the weight    */
+/* neg_scale:                                                                  */
+/*   J = sum_b [ log sigma(x_b . c_ctx_b) + neg_scale sum_n log sigma(-x_b . c_n) ] */
+/* Positive part exactly as in oracle_train_batch (full precision).            */
+/* Negative part, with q() = round-to-nearest-even to bfloat16 when            */
+/* bf16_inputs != 0 (identity otherwise):                                      */
+/*   S_bn = <q(x_b), q(c_n)>;  G_bn = q(fp32(-neg_scale sigma(S_bn)))           */
+/*   DX[src_b] += lr sum_n G_bn q(c_n);   DC[neg_n] += lr sum_b G_bn q(x_b)      */
+/* All deltas from the pre-batch tables, summed, applied once.  *loss_out (if  */
+/* not NULL) receives sum_b [softplus(-s_b0) + neg_scale sum_n softplus(S_bn)]. */
+/* ------------------------------------------------------------------------- */
+static float bf16_rne(float x)
+{
+    uint32_t u;
+    memcpy(&u, &x, 4);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    u &= 0xFFFF0000u;
+    float r;
+    memcpy(&r, &u, 4);
+    return r;
+}
+
+int oracle_train_batch_shared(float* X, float* C, int64_t V, int32_t d, const int32_t* pairs, int64_t B,
+                              const int32_t* negs, int32_t N, float lr_f, float neg_scale_f,
+                              int32_t bf16_inputs, double* loss_out)
+{
+    const double lr = (double)lr_f, neg_scale = (double)neg_scale_f;
+    for (int64_t b = 0; b < B; ++b)
+        if (pairs[2 * b] < 0 || pairs[2 * b] >= V || pairs[2 * b + 1] < 0 || pairs[2 * b + 1] >= V) return -1;
+    for (int32_t n = 0; n < N; ++n)
+        if (negs[n] < 0 || negs[n] >= V) return -1;
+    delta_map DX, DC;
+    if (dm_init(&DX, V, B, d) || dm_init(&DC, V, B + N, d)) { dm_free(&DX); dm_free(&DC); return -2; }
+    double* xq = (double*)malloc((size_t)d * sizeof(double));
+    double* cq = (double*)malloc((size_t)d * sizeof(double));
+    if (!xq || !cq) { free(xq); free(cq); dm_free(&DX); dm_free(&DC); return -2; }
+    double loss = 0.0;
+
+    for (int64_t b = 0; b < B; ++b) {
+        const int64_t src = pairs[2 * b], ctx = pairs[2 * b + 1];
+        const float* x = X + src * (int64_t)d;
+        const float* c0 = C + ctx * (int64_t)d;
+        double* dx = dm_row(&DX, src);
+        /* positive pair, label 1 */
+        double s0 = 0.0;
+        for (int32_t i = 0; i < d; ++i) s0 += (double)x[i] * (double)c0[i];
+        const double g0 = 1.0 - sigmoid(s0);
+        loss += softplus(-s0);
+        double* dc0 = dm_row(&DC, ctx);
+        for (int32_t i = 0; i < d; ++i) {
+            dx[i] += lr * g0 * (double)c0[i];
+            dc0[i] += lr * g0 * (double)x[i];
+        }
+        /* shared negatives, label 0, weight neg_scale */
+        for (int32_t i = 0; i < d; ++i) xq[i] = bf16_inputs ? (double)bf16_rne(x[i]) : (double)x[i];
+        for (int32_t n = 0; n < N; ++n) {
+            const float* c = C + (int64_t)negs[n] * d;
+            double S = 0.0;
+            for (int32_t i = 0; i < d; ++i) {
+                cq[i] = bf16_inputs ? (double)bf16_rne(c[i]) : (double)c[i];
+                S += xq[i] * cq[i];
+            }
+            loss += neg_scale * softplus(S);
+            double G = -neg_scale * sigmoid(S);
+            if (bf16_inputs) G = (double)bf16_rne((float)G);
+            double* dc = dm_row(&DC, negs[n]);
+            for (int32_t i = 0; i < d; ++i) {
+                dx[i] += lr * G * cq[i];
+                dc[i] += lr * G * xq[i];
+            }
+        }
+    }
+    for (int64_t t = 0; t < DX.count; ++t) {
+        float* row = X + DX.rows[t] * (int64_t)d;
+        for (int32_t i = 0; i < d; ++i) row[i] = (float)((double)row[i] + DX.acc[t * (int64_t)d + i]);
+    }
+    for (int64_t t = 0; t < DC.count; ++t) {
+        float* row = C + DC.rows[t] * (int64_t)d;
+        for (int32_t i = 0; i < d; ++i) row[i] = (float)((double)row[i] + DC.acc[t * (int64_t)d + i]);
+    }
+    if (loss_out) *loss_out = loss;
+    free(xq); free(cq);
+    dm_free(&DX); dm_free(&DC);
+    return 0;
+}
