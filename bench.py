@@ -11,6 +11,8 @@ Workloads (synthetic R-MAT stand-ins for the paper's graphs):
   c2  1 M nodes / 20 M edges, walks of 80, window 5, dim 128, K=5, batch 65536.
   c4  20 M nodes, dim 512, K=10, batch 32768.
   c1  10 k nodes, dim 128, K=5, batch 4096 (the parity configuration; cache resident).
+  c5  shared-negative mode: 50 M nodes (R-MAT a=0.65), dim 256, batches of 8192 pairs that share 1024
+      negatives (bf16 MFMA tiles, fp32 accumulate and update); its roofline is the matrix cores'.
 
 Prints one JSON line.  --gpus above 1 is refused: this build is single-GPU.
 """
@@ -36,13 +38,16 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per train-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see
 # profiles/), scaled by the factor a plain copy kernel of known size reads on the same counters.
 # None = not measured for that workload.
-TRAFFIC_BYTES_PER_LAUNCH = {"c1": None, "c2": None, "c3": 564.2e6, "c4": None}
+TRAFFIC_BYTES_PER_LAUNCH = {"c1": None, "c2": None, "c3": 564.2e6, "c4": None, "c5": None}
+MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 WORKLOADS = {
     "c1": dict(V=10_000, edges=100_000, d=128, K=5, B=4096, grid=1, abc=(0.57, 0.19, 0.19), walk=(40, 5), seed=0),
     "c2": dict(V=1_000_000, edges=20_000_000, d=128, K=5, B=65536, grid=1, abc=(0.57, 0.19, 0.19), walk=(80, 5), seed=1),
     "c3": dict(V=100_000_000, edges=2_000_000_000, d=128, K=5, B=65536, grid=4, abc=(0.57, 0.19, 0.19), walk=None, seed=2),
     "c4": dict(V=20_000_000, edges=400_000_000, d=512, K=10, B=32768, grid=1, abc=(0.57, 0.19, 0.19), walk=None, seed=3),
+    "c5": dict(V=50_000_000, edges=1_000_000_000, d=256, K=0, B=8192, grid=1, abc=(0.65, 0.15, 0.15), walk=None, seed=4,
+               shared_negatives=1024),
 }
 
 
@@ -121,8 +126,13 @@ def main():
     t0 = time.time()
     vertex = torch.empty((V, d), dtype=torch.float32, device=dev)
     context = torch.empty((V, d), dtype=torch.float32, device=dev)
-    workspace = torch.empty(ne.ne_workspace_bytes(d, B, K), dtype=torch.uint8, device=dev)
-    tables = ne.ne_create_tables(vertex, context, seed, init=True, max_batch=B, max_negatives=K, workspace=workspace)
+    N = w.get("shared_negatives", 0)
+    if N:
+        workspace = torch.empty(ne.ne_shared_workspace_bytes(d, B, N), dtype=torch.uint8, device=dev)
+        tables = ne.ne_create_tables(vertex, context, seed, init=True)
+    else:
+        workspace = torch.empty(ne.ne_workspace_bytes(d, B, K), dtype=torch.uint8, device=dev)
+        tables = ne.ne_create_tables(vertex, context, seed, init=True, max_batch=B, max_negatives=K, workspace=workspace)
     # one alias table per context block (a GPU's context partition is fixed; negatives come from it)
     block = bp.block_rows
     deg_host = degree.to(torch.int64).clamp_(max=2**32 - 1).cpu().numpy().astype(np.uint32)
@@ -144,6 +154,10 @@ def main():
         library as one ne_train_block call (the id-only work of batch i+1 then rides in the kernels
         of batch i); --per-batch calls ne_train_batch once per batch instead."""
         i = first
+        while N and i < last:          # shared-negative mode: one call per batch
+            s, n, _, bj = sched[i]
+            ne.ne_train_batch_shared(tables, aliases[bj], pairs[s:s + n], N, float(lrs[i]), 5.0 / N, i, workspace)
+            i += 1
         while i < last:
             s, n, bi, bj = sched[i]
             k = i + 1
@@ -166,9 +180,24 @@ def main():
     ne.ne_profile_enable(tables, 0, 0)
 
     pairs_per_s = args.steps * B / elapsed
-    bpp = algorithmic_bytes_per_pair(d, K)
     avg_kernel_ms = kern_ms / max(kern_n, 1)
-    achieved = (bpp * B) / (avg_kernel_ms * 1e-3) / 1e9 if kern_n else None
+    if N:
+        # two gathered rows per pair and the N shared rows per batch, read and written once; ids
+        bpp = 2 * (2 * B + N) * 4 * d / B + 8
+        flops = 2 * 2.0 * B * N * d          # S and dX products of the scores kernel
+        achieved = flops / (avg_kernel_ms * 1e-3) / 1e12 if kern_n else None
+        roofline = {"bound": "mfma", "kernel": "scores_kernel", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": (achieved / MFMA_BF16_PEAK_TFLOPS) if achieved else None, "traffic": None,
+                    "flops_per_launch": flops, "avg_kernel_ms": avg_kernel_ms, "kernel_samples": kern_n}
+        call = "ne_train_batch_shared per step"
+    else:
+        bpp = algorithmic_bytes_per_pair(d, K)
+        achieved = (bpp * B) / (avg_kernel_ms * 1e-3) / 1e9 if kern_n else None
+        roofline = {"bound": "hbm", "kernel": "train_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
+                    "traffic": TRAFFIC_BYTES_PER_LAUNCH[name], "bytes_per_launch": bpp * B,
+                    "avg_kernel_ms": avg_kernel_ms, "kernel_samples": kern_n}
+        call = "ne_train_batch per step" if args.per_batch else "ne_train_block per bucket run"
     result = {
         "metric": "positive edge samples/sec on 1 MI355X + achieved HBM GB/s vs peak",
         "value": pairs_per_s,
@@ -180,15 +209,11 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "bf16" if N else "f32",
         "data": "synthetic",
-        "config": {"workload": name, "nodes": V, "dim": d, "negatives": K, "batch": B, "block_grid": f"{grid}x{grid}",
-                   "call": "ne_train_batch per step" if args.per_batch else "ne_train_block per bucket run",
-                   "end_to_end_GBps": pairs_per_s * bpp / 1e9},
-        "roofline": {"bound": "hbm", "kernel": "train_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
-                     "traffic": TRAFFIC_BYTES_PER_LAUNCH[name], "bytes_per_launch": bpp * B,
-                     "avg_kernel_ms": avg_kernel_ms, "kernel_samples": kern_n},
+        "config": {"workload": name, "nodes": V, "dim": d, "negatives": N if N else K, "batch": B,
+                   "block_grid": f"{grid}x{grid}", "call": call, "end_to_end_GBps": pairs_per_s * bpp / 1e9},
+        "roofline": roofline,
     }
 
     if not args.no_cpu_baseline:
@@ -215,9 +240,15 @@ def cpu_baseline(w, deg_host, bp, sched, n_cpu_batches):
         p = bp.pairs[s:s + n].cpu().numpy()
         return np.ascontiguousarray(p % fold if V != fold else p, dtype=np.int32)
 
+    N = w.get("shared_negatives", 0)
+
     def run(i, p):
-        neg = oracle.sample_negatives(seed, i * B, p.shape[0], K, thr, alias, 0)
-        oracle.train_batch(X, C, p, neg, 0.025)
+        if N:
+            negs = oracle.sample_shared_negatives(seed, i, N, thr, alias, 0)
+            oracle.train_batch_shared(X, C, p, negs, 0.025, 5.0 / N, bf16_inputs=True)
+        else:
+            neg = oracle.sample_negatives(seed, i * B, p.shape[0], K, thr, alias, 0)
+            oracle.train_batch(X, C, p, neg, 0.025)
 
     p0 = batch(0)
     t0 = time.perf_counter()

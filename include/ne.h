@@ -126,6 +126,32 @@ ne_status ne_train_block(ne_tables* tables, const ne_alias* alias, const int32_t
                          uint64_t sample_base, int32_t* neg_out_dev, void* hip_stream);
 
 /*
+ * Shared-negative step: the formulation the paper cites as related work (Sec. VI-B), where all pairs
+ * of a mini-batch share one set of negatives so that scoring and both gradient products become dense
+ * matrix products.  Every one of the B pairs is scored against the same N negative context rows;
+ * negative terms carry the weight neg_scale:
+ *   J = sum_b [ log sigmoid(x_b . c_ctx_b) + neg_scale * sum_n log sigmoid(-x_b . c_n) ]
+ * and the tables move by lr * dJ, minibatch-synchronously (pre-batch tables, duplicates summed).
+ * Negative n is the alias draw for Philox(key = seed, counter = (batch_index_lo, batch_index_hi, n, 2)).
+ * Precision: the positive pair is computed in fp32.  For the dense part the gathered rows are rounded
+ * to bfloat16 (nearest even), S = Xq . Cq^T accumulates in fp32 on the matrix cores,
+ * G = -neg_scale * sigmoid(S) is formed in fp32 and rounded to bfloat16, and G . Cq and G^T . Xq
+ * accumulate in fp32; the tables stay fp32 and are updated with fp32 atomic adds.
+ *   dim must be 64, 128 or 256; 1 <= B <= 2^20; N a multiple of 128 in [128, 65536].
+ *   workspace_dev : device scratch, 256-byte aligned, at least ne_shared_workspace_bytes(dim, B, N)
+ *                   bytes, overwritten; needs no initialisation and carries nothing between calls.
+ *   neg_out_dev   : NULL, or device int32[N] receiving the negative ids.
+ *   loss_sum_dev  : NULL, or device double (caller-zeroed) to which the batch's summed loss at the
+ *                   pre-batch tables is added: sum_b [softplus(-s_b0) + neg_scale sum_n softplus(S_bn)].
+ * B == 0 is a no-op.  Errors: NE_ERR_ARG, NE_ERR_STATE, NE_ERR_HIP.
+ */
+size_t ne_shared_workspace_bytes(int32_t dim, int64_t B, int32_t N);
+ne_status ne_train_batch_shared(ne_tables* tables, const ne_alias* alias, const int32_t* pairs_dev,
+                                int64_t B, int32_t N, float lr, float neg_scale, uint64_t batch_index,
+                                void* workspace_dev, size_t workspace_bytes, int32_t* neg_out_dev,
+                                double* loss_sum_dev, void* hip_stream);
+
+/*
  * Loss of a batch at the current tables with the same negatives ne_train_batch would draw; nothing
  * is updated.  Adds  sum_b [ -log sigmoid(s_b0) - sum_k log sigmoid(-s_bk) ]  (fp32 terms, fp64 sum)
  * to *loss_sum_dev.
@@ -148,7 +174,8 @@ ne_status ne_validate_pairs(const ne_tables* tables, const int32_t* pairs_dev, i
  * Measurement hooks (instrumentation for benchmarks, not part of the method).  After
  * ne_profile_enable(t, n, max_samples) with n > 0, every n-th ne_train_batch call records a HIP event
  * on the stream immediately before and after its train kernel (the kernel that gathers the rows,
- * scores and writes them back), for at most max_samples (<= 65536) calls; n = 0 switches it off.
+ * scores and writes them back; for ne_train_batch_shared: the scores kernel with the S and dX
+ * products), for at most max_samples (<= 65536) calls; n = 0 switches it off.
  * ne_profile_read waits for the recorded events, stores the sum of the kernel durations in
  * milliseconds in *total_ms_host and their number in *samples_host (both host), and starts over.
  */

@@ -26,7 +26,7 @@ NE_MAX_BATCH = 1 << 22
 
 EXPORTS = (
     "ne_create_tables", "ne_build_neg_alias", "ne_workspace_bytes", "ne_train_batch", "ne_train_block",
-    "ne_eval_loss",
+    "ne_shared_workspace_bytes", "ne_train_batch_shared", "ne_eval_loss",
     "ne_validate_pairs", "ne_profile_enable", "ne_profile_read", "ne_destroy_tables", "ne_destroy_alias", "ne_last_error",
 )
 
@@ -61,6 +61,11 @@ def lib() -> ctypes.CDLL:
     L.ne_train_batch.restype = c.c_int
     L.ne_train_block.argtypes = [vp, vp, vp, c.c_int64, c.c_int64, c.c_int32, c.POINTER(c.c_float), c.c_uint64, vp, vp]
     L.ne_train_block.restype = c.c_int
+    L.ne_shared_workspace_bytes.argtypes = [c.c_int32, c.c_int64, c.c_int32]
+    L.ne_shared_workspace_bytes.restype = c.c_size_t
+    L.ne_train_batch_shared.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_float, c.c_float, c.c_uint64, vp,
+                                        c.c_size_t, vp, vp, vp]
+    L.ne_train_batch_shared.restype = c.c_int
     L.ne_eval_loss.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_uint64, vp, vp, vp]
     L.ne_eval_loss.restype = c.c_int
     L.ne_validate_pairs.argtypes = [vp, vp, c.c_int64, vp, vp]
@@ -197,6 +202,25 @@ def ne_train_block(tables: Tables, alias: Alias | None, pairs: torch.Tensor, B: 
         raise TypeError("neg_out needs n_pairs*K int32 elements")
     _check(lib().ne_train_block(tables.handle, alias.handle if alias else None, pp, n_pairs, B, K, arr, sample_base,
                                 np_, _stream_ptr(stream)))
+
+
+def ne_shared_workspace_bytes(dim: int, B: int, N: int) -> int:
+    return int(lib().ne_shared_workspace_bytes(dim, B, N))
+
+
+def ne_train_batch_shared(tables: Tables, alias: Alias, pairs: torch.Tensor, N: int, lr: float, neg_scale: float,
+                          batch_index: int, workspace: torch.Tensor, neg_out: torch.Tensor | None = None,
+                          loss_sum: torch.Tensor | None = None, stream=None) -> None:
+    """Shared-negative step: every pair of pairs int32 [B][2] (CUDA) against the same N negatives."""
+    B = int(pairs.shape[0])
+    pp = _dev_ptr(pairs, torch.int32, "pairs")
+    wp = _dev_ptr(workspace, torch.uint8, "workspace")
+    np_ = _dev_ptr(neg_out, torch.int32, "neg_out")
+    lp = _dev_ptr(loss_sum, torch.float64, "loss_sum")
+    if neg_out is not None and neg_out.numel() < N:
+        raise TypeError("neg_out needs N int32 elements")
+    _check(lib().ne_train_batch_shared(tables.handle, alias.handle if alias else None, pp, B, N, lr, neg_scale,
+                                       batch_index, wp, workspace.numel(), np_, lp, _stream_ptr(stream)))
 
 
 def ne_eval_loss(tables: Tables, alias: Alias | None, pairs: torch.Tensor, K: int, sample_base: int,

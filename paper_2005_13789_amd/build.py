@@ -7,7 +7,7 @@ import sys
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
-SRC = os.path.join(PKG, "csrc", "ne.hip")
+SRCS = [os.path.join(PKG, "csrc", "ne.hip"), os.path.join(PKG, "csrc", "ne_shared.hip")]
 OUT = os.path.join(PKG, "libne.so")
 
 HIPCC_FLAGS = [
@@ -22,7 +22,7 @@ HIPCC_FLAGS = [
 
 
 def build(verbose: bool = False) -> str:
-    cmd = ["hipcc", *HIPCC_FLAGS, SRC, "-o", OUT]
+    cmd = ["hipcc", *HIPCC_FLAGS, *SRCS, "-o", OUT]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -1,0 +1,498 @@
+// Shared-negative SGNS step for MI355X (gfx950): ne_train_batch_shared.
+//
+// All B pairs of a batch are scored against the same N negative rows, which turns scoring and both
+// gradient products into dense contractions (the level-3 formulation the paper cites as related
+// work, Sec. VI-B):
+//     S  = Xq . Cq^T            [B x d] . [d x N]      scores
+//     G  = -neg_scale sigma(S)                          coefficients (rounded to bf16)
+//     dX = G . Cq               [B x N] . [N x d]      gradient of the source rows
+//     dC = G^T . Xq             [N x B] . [B x d]      gradient of the negative rows
+// with Xq, Cq the gathered rows rounded to bf16 and fp32 accumulation on the matrix cores
+// (v_mfma_f32_32x32x16_bf16).  The positive pair of every sample is handled in full fp32.
+//
+// Four kernels per batch:
+//   stage   gathers and rounds the rows, draws the N negatives, does the positive pairs in fp32 and
+//           stages their deltas; the tables are only read.
+//   scores  one workgroup per 64 pairs: S tile by tile on MFMA, sigmoid in registers, G to LDS (and
+//           transposed to memory for the dC product), dX accumulated on MFMA over all N negatives.
+//   dctx    dC = G^T . Xq on MFMA, split over the batch dimension into partial sums.
+//   update  adds every staged delta to the tables with fp32 atomics (consecutive dwords per lane
+//           group).  Nothing reads the tables any more at that point, so duplicates simply add up.
+#include <hip/hip_bf16.h>
+
+#include "ne_internal.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kRowTile = 64;     // pairs per workgroup in the scores kernel
+constexpr int kNegChunk = 64;    // negatives per LDS chunk in the scores kernel
+constexpr int kSplit = 8;        // partial sums of the dC product
+constexpr int kBatchPad = 128;   // the padded batch is a multiple of this
+
+__device__ __forceinline__ uint16_t to_bf16(float x)
+{
+    uint32_t u = __float_as_uint(x);
+    u += 0x7FFFu + ((u >> 16) & 1u);   // round to nearest even
+    return static_cast<uint16_t>(u >> 16);
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+struct SharedWs {
+    uint16_t* Xq;    // [Bp][d]   bf16 source rows (zero beyond B)
+    uint16_t* XqT;   // [d][Bp]
+    uint16_t* Cq;    // [N][d]    bf16 negative rows
+    uint16_t* CqT;   // [d][N]
+    uint16_t* GT;    // [N][Bp]   bf16 coefficients, transposed
+    float* dxp;      // [Bp][d]   lr * g0 * c_ctx          (positive pair, source side)
+    float* uctx;     // [Bp][d]   lr * g0 * x              (positive pair, context side)
+    float* dXn;      // [Bp][d]   G . Cq
+    float* dCp;      // [kSplit][N][d] partial sums of G^T . Xq
+    int32_t* negids; // [N]
+    int64_t Bp;
+    size_t total;
+};
+
+bool shared_layout(int32_t dim, int64_t B, int32_t N, char* base, SharedWs* w)
+{
+    if (!(dim == 64 || dim == 128 || dim == 256) || B < 1 || B > (1 << 20) || N < 128 || N > 65536 || N % 128 != 0)
+        return false;
+    const size_t Bp = static_cast<size_t>((B + kBatchPad - 1) / kBatchPad) * kBatchPad;
+    auto up = [](size_t v) { return (v + 255) & ~static_cast<size_t>(255); };
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char* p = base + off; off = up(off + bytes); return p; };
+    const size_t d = static_cast<size_t>(dim), n = static_cast<size_t>(N);
+    w->Bp = static_cast<int64_t>(Bp);
+    w->Xq = reinterpret_cast<uint16_t*>(take(Bp * d * 2));
+    w->XqT = reinterpret_cast<uint16_t*>(take(Bp * d * 2));
+    w->Cq = reinterpret_cast<uint16_t*>(take(n * d * 2));
+    w->CqT = reinterpret_cast<uint16_t*>(take(n * d * 2));
+    w->GT = reinterpret_cast<uint16_t*>(take(n * Bp * 2));
+    w->dxp = reinterpret_cast<float*>(take(Bp * d * 4));
+    w->uctx = reinterpret_cast<float*>(take(Bp * d * 4));
+    w->dXn = reinterpret_cast<float*>(take(Bp * d * 4));
+    w->dCp = reinterpret_cast<float*>(take(static_cast<size_t>(kSplit) * n * d * 4));
+    w->negids = reinterpret_cast<int32_t*>(take(n * 4));
+    w->total = off;
+    return true;
+}
+
+// ---------------------------------------------------------------------------------------------
+// stage kernel.  One lane group of G = D/8 lanes per row: groups [0, Bp) are the pairs, groups
+// [Bp, Bp+N) the negatives.  Lane lg holds the float4 chunks lg and lg+G of its row.
+// ---------------------------------------------------------------------------------------------
+struct StageArgs {
+    const float4* X;
+    const float4* C;
+    const int2* pairs;
+    int64_t B, Bp;
+    int32_t N;
+    float lr;
+    uint64_t batch_index;
+    uint32_t k0, k1;
+    const uint2* alias;
+    uint64_t alias_n;
+    int32_t alias_base;
+    SharedWs w;
+    int32_t* neg_out;
+    double* loss;
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void stage_kernel(StageArgs a)
+{
+    constexpr int G = D / 8;
+    constexpr int GROUPS = 256 / G;
+    constexpr int D4 = D / 4;
+    const int lg = threadIdx.x & (G - 1);
+    const int64_t gidx = static_cast<int64_t>(blockIdx.x) * GROUPS + threadIdx.x / G;
+    float loss_term = 0.0f;
+    if (gidx < a.Bp) {
+        const int64_t b = gidx;
+        uint2* xq = reinterpret_cast<uint2*>(a.w.Xq + b * D);
+        if (b < a.B) {
+            const int2 pr = a.pairs[b];
+            const float4* xrow = a.X + static_cast<int64_t>(pr.x) * D4;
+            const float4* crow = a.C + static_cast<int64_t>(pr.y) * D4;
+            float4 x[2], c[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) { x[i] = xrow[lg + i * G]; c[i] = crow[lg + i * G]; }
+            const float s0 = group_sum<G>(dot4(x[0], c[0]) + dot4(x[1], c[1]));
+            const float g0 = a.lr * (1.0f - sigmoidf(s0));
+            if (lg == 0) loss_term = softplusf(-s0);
+            float4* dxp = reinterpret_cast<float4*>(a.w.dxp + b * D);
+            float4* uctx = reinterpret_cast<float4*>(a.w.uctx + b * D);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int ci = lg + i * G;
+                dxp[ci] = make_float4(g0 * c[i].x, g0 * c[i].y, g0 * c[i].z, g0 * c[i].w);
+                uctx[ci] = make_float4(g0 * x[i].x, g0 * x[i].y, g0 * x[i].z, g0 * x[i].w);
+                xq[ci] = make_uint2(to_bf16(x[i].x) | (static_cast<uint32_t>(to_bf16(x[i].y)) << 16),
+                                    to_bf16(x[i].z) | (static_cast<uint32_t>(to_bf16(x[i].w)) << 16));
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) xq[lg + i * G] = make_uint2(0u, 0u);   // padding rows score zero
+        }
+    } else if (gidx < a.Bp + a.N) {
+        const int32_t j = static_cast<int32_t>(gidx - a.Bp);
+        const uint4 r = philox4x32_10(make_uint4(static_cast<uint32_t>(a.batch_index), static_cast<uint32_t>(a.batch_index >> 32),
+                                                 static_cast<uint32_t>(j), kStreamSharedNegative), a.k0, a.k1);
+        const int32_t id = a.alias_base + alias_draw(r, a.alias, a.alias_n);
+        if (lg == 0) {
+            a.w.negids[j] = id;
+            if (a.neg_out) a.neg_out[j] = id;
+        }
+        const float4* crow = a.C + static_cast<int64_t>(id) * D4;
+        uint2* cq = reinterpret_cast<uint2*>(a.w.Cq + static_cast<int64_t>(j) * D);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int ci = lg + i * G;
+            const float4 c = crow[ci];
+            const uint16_t h0 = to_bf16(c.x), h1 = to_bf16(c.y), h2 = to_bf16(c.z), h3 = to_bf16(c.w);
+            cq[ci] = make_uint2(h0 | (static_cast<uint32_t>(h1) << 16), h2 | (static_cast<uint32_t>(h3) << 16));
+            uint16_t* ct = a.w.CqT + static_cast<int64_t>(4 * ci) * a.N + j;
+            ct[0] = h0; ct[a.N] = h1; ct[2 * static_cast<int64_t>(a.N)] = h2; ct[3 * static_cast<int64_t>(a.N)] = h3;
+        }
+    }
+    if (a.loss) {   // uniform over the grid
+        __shared__ double sh[4];
+        float l = loss_term;
+        for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off, 64);
+        if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = static_cast<double>(l);
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const double t = sh[0] + sh[1] + sh[2] + sh[3];
+            if (t != 0.0) atomicAdd(a.loss, t);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// scores kernel: one workgroup (4 wavefronts) per 64 pairs.
+//   wavefront w: row half rh = w & 1 (32 pairs); column half ch = w >> 1
+//   S tile   : pairs rh*32.. x negatives ch*32.. of the current 64-negative chunk   (1 MFMA tile)
+//   dX tiles : pairs rh*32.. x columns ch*D/2 .. ch*D/2 + D/2                        (D/64 tiles)
+// MFMA 32x32x16 operand layout (checked on hardware): lane l supplies row/column l%32 and the 8
+// consecutive k values (l/32)*8..+7; accumulator element i is row (i/4)*8 + (l/32)*4 + i%4, column l%32.
+// LDS rows are padded by 8 bf16 so that the 16-byte fragment reads of 32 rows spread over all banks.
+// ---------------------------------------------------------------------------------------------
+struct ScoresArgs {
+    SharedWs w;
+    int64_t B;
+    int32_t N;
+    float neg_scale;
+    double* loss;
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void scores_kernel(ScoresArgs a)
+{
+    constexpr int XP = D + 8;            // pitch of Xs and Cs rows (bf16)
+    constexpr int TP = kNegChunk + 8;    // pitch of CTs and Gs rows
+    constexpr int DT = D / 64;           // dX tiles per wavefront
+    extern __shared__ uint16_t lds[];
+    uint16_t* Xs = lds;                              // [64][XP]
+    uint16_t* Cs = Xs + kRowTile * XP;               // [64][XP]
+    uint16_t* CTs = Cs + kNegChunk * XP;             // [D][TP]
+    uint16_t* Gs = CTs + D * TP;                     // [64][TP]
+    const int tid = threadIdx.x;
+    const int l = tid & 63, w = tid >> 6;
+    const int rh = w & 1, ch = w >> 1;
+    const int64_t b0 = static_cast<int64_t>(blockIdx.x) * kRowTile;
+    const int64_t Bp = a.w.Bp;
+
+    // the 64 source rows of this workgroup
+    for (int c = tid; c < kRowTile * (D / 8); c += 256) {
+        const int r = c / (D / 8), q = c % (D / 8);
+        *reinterpret_cast<uint4*>(Xs + r * XP + q * 8) = *reinterpret_cast<const uint4*>(a.w.Xq + (b0 + r) * D + q * 8);
+    }
+    __syncthreads();
+    // by-product: the transposed copy the dC product reads
+    for (int col = tid; col < D; col += 256) {
+        uint16_t* out = a.w.XqT + static_cast<int64_t>(col) * Bp + b0;
+#pragma unroll
+        for (int r0 = 0; r0 < kRowTile; r0 += 8) {
+            uint32_t p[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                p[i] = Xs[(r0 + 2 * i) * XP + col] | (static_cast<uint32_t>(Xs[(r0 + 2 * i + 1) * XP + col]) << 16);
+            *reinterpret_cast<uint4*>(out + r0) = make_uint4(p[0], p[1], p[2], p[3]);
+        }
+    }
+
+    f32x16 acc_dx[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc_dx[t][i] = 0.0f;
+    float loss = 0.0f;
+
+    for (int n0 = 0; n0 < a.N; n0 += kNegChunk) {
+        // this chunk's negative rows, and their transpose
+        for (int c = tid; c < kNegChunk * (D / 8); c += 256) {
+            const int r = c / (D / 8), q = c % (D / 8);
+            *reinterpret_cast<uint4*>(Cs + r * XP + q * 8) =
+                *reinterpret_cast<const uint4*>(a.w.Cq + static_cast<int64_t>(n0 + r) * D + q * 8);
+        }
+        for (int c = tid; c < D * (kNegChunk / 8); c += 256) {
+            const int r = c / (kNegChunk / 8), q = c % (kNegChunk / 8);
+            *reinterpret_cast<uint4*>(CTs + r * TP + q * 8) =
+                *reinterpret_cast<const uint4*>(a.w.CqT + static_cast<int64_t>(r) * a.N + n0 + q * 8);
+        }
+        __syncthreads();
+
+        // S = Xq . Cq^T for 32 pairs x 32 negatives
+        f32x16 s;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[i] = 0.0f;
+        const uint16_t* xa = Xs + (rh * 32 + (l & 31)) * XP + (l >> 5) * 8;
+        const uint16_t* cb = Cs + (ch * 32 + (l & 31)) * XP + (l >> 5) * 8;
+#pragma unroll 4
+        for (int k0 = 0; k0 < D; k0 += 16) {
+            const bf16x8 av = as_bf16x8(*reinterpret_cast<const uint4*>(xa + k0));
+            const bf16x8 bv = as_bf16x8(*reinterpret_cast<const uint4*>(cb + k0));
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, s, 0, 0, 0);
+        }
+        // G = -neg_scale * sigmoid(S), zero for padding rows; into LDS as bf16
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int row = rh * 32 + (i >> 2) * 8 + (l >> 5) * 4 + (i & 3);
+            const int col = ch * 32 + (l & 31);
+            const bool valid = b0 + row < a.B;
+            const float g = valid ? -a.neg_scale * sigmoidf(s[i]) : 0.0f;
+            if (a.loss && valid) loss += a.neg_scale * softplusf(s[i]);
+            Gs[row * TP + col] = to_bf16(g);
+        }
+        __syncthreads();
+
+        // G^T to memory: 64 negatives x 64 pairs, 128 contiguous bytes per negative
+        {
+            const int neg = tid >> 2, part = tid & 3;
+            uint32_t p[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                p[i] = Gs[(part * 16 + 2 * i) * TP + neg] | (static_cast<uint32_t>(Gs[(part * 16 + 2 * i + 1) * TP + neg]) << 16);
+            uint4* out = reinterpret_cast<uint4*>(a.w.GT + static_cast<int64_t>(n0 + neg) * Bp + b0 + part * 16);
+            out[0] = make_uint4(p[0], p[1], p[2], p[3]);
+            out[1] = make_uint4(p[4], p[5], p[6], p[7]);
+        }
+        // dX += G . Cq for 32 pairs x D/2 columns over the 64 negatives of the chunk
+        const uint16_t* ga = Gs + (rh * 32 + (l & 31)) * TP + (l >> 5) * 8;
+#pragma unroll
+        for (int kk = 0; kk < kNegChunk; kk += 16) {
+            const bf16x8 av = as_bf16x8(*reinterpret_cast<const uint4*>(ga + kk));
+#pragma unroll
+            for (int t = 0; t < DT; ++t) {
+                const uint16_t* tb = CTs + (ch * (D / 2) + t * 32 + (l & 31)) * TP + (l >> 5) * 8 + kk;
+                acc_dx[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, as_bf16x8(*reinterpret_cast<const uint4*>(tb)),
+                                                                    acc_dx[t], 0, 0, 0);
+            }
+        }
+        __syncthreads();   // Cs, CTs, Gs are rewritten by the next chunk
+    }
+
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int row = rh * 32 + (i >> 2) * 8 + (l >> 5) * 4 + (i & 3);
+            const int col = ch * (D / 2) + t * 32 + (l & 31);
+            a.w.dXn[(b0 + row) * D + col] = acc_dx[t][i];
+        }
+    if (a.loss) {
+        __shared__ double sh[4];
+        for (int off = 32; off > 0; off >>= 1) loss += __shfl_xor(loss, off, 64);
+        if (l == 0) sh[w] = static_cast<double>(loss);
+        __syncthreads();
+        if (tid == 0) atomicAdd(a.loss, sh[0] + sh[1] + sh[2] + sh[3]);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// dctx kernel: dC = G^T . Xq.  Workgroup tile 128 negatives x 64 columns, one k-range of the batch
+// per blockIdx.z; wavefront w: negatives w*32.., two 32x32 tiles side by side.  Operands come
+// straight from memory (both are k-contiguous there and small enough to stay in L2).
+// ---------------------------------------------------------------------------------------------
+struct DctxArgs {
+    SharedWs w;
+    int32_t N, D;
+};
+
+__global__ __launch_bounds__(256) void dctx_kernel(DctxArgs a)
+{
+    const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t Bp = a.w.Bp;
+    const int64_t kc = Bp / kSplit;
+    const int64_t kbeg = static_cast<int64_t>(blockIdx.z) * kc;
+    const int n0 = blockIdx.x * 128 + w * 32;
+    const int d0 = blockIdx.y * 64;
+    f32x16 acc[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[t][i] = 0.0f;
+    const uint16_t* ga = a.w.GT + static_cast<int64_t>(n0 + (l & 31)) * Bp + kbeg + (l >> 5) * 8;
+    const uint16_t* xb0 = a.w.XqT + static_cast<int64_t>(d0 + (l & 31)) * Bp + kbeg + (l >> 5) * 8;
+    const uint16_t* xb1 = xb0 + 32 * Bp;
+#pragma unroll 4
+    for (int64_t k0 = 0; k0 < kc; k0 += 16) {
+        const bf16x8 av = as_bf16x8(*reinterpret_cast<const uint4*>(ga + k0));
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, as_bf16x8(*reinterpret_cast<const uint4*>(xb0 + k0)), acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, as_bf16x8(*reinterpret_cast<const uint4*>(xb1 + k0)), acc[1], 0, 0, 0);
+    }
+    float* out = a.w.dCp + static_cast<int64_t>(blockIdx.z) * a.N * a.D;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int row = n0 + (i >> 2) * 8 + (l >> 5) * 4 + (i & 3);
+            const int col = d0 + t * 32 + (l & 31);
+            out[static_cast<int64_t>(row) * a.D + col] = acc[t][i];
+        }
+}
+
+// ---------------------------------------------------------------------------------------------
+// update kernel: one lane group of G = D/8 lanes per pair / per negative; lane lg owns elements
+// lg + m*G, so every atomic instruction of a group covers consecutive dwords.
+// ---------------------------------------------------------------------------------------------
+struct UpdateArgs {
+    float* X;
+    float* C;
+    const int2* pairs;
+    int64_t B;
+    int32_t N;
+    float lr;
+    SharedWs w;
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void update_shared_kernel(UpdateArgs a)
+{
+    constexpr int G = D / 8;
+    constexpr int GROUPS = 256 / G;
+    const int lg = threadIdx.x & (G - 1);
+    const int64_t gidx = static_cast<int64_t>(blockIdx.x) * GROUPS + threadIdx.x / G;
+    if (gidx < a.B) {
+        const int2 pr = a.pairs[gidx];
+        float* xrow = a.X + static_cast<int64_t>(pr.x) * D;
+        float* crow = a.C + static_cast<int64_t>(pr.y) * D;
+        const float* dxp = a.w.dxp + gidx * D;
+        const float* dxn = a.w.dXn + gidx * D;
+        const float* uctx = a.w.uctx + gidx * D;
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+            const int e = lg + m * G;
+            unsafeAtomicAdd(xrow + e, fmaf(a.lr, dxn[e], dxp[e]));
+            unsafeAtomicAdd(crow + e, uctx[e]);
+        }
+    } else if (gidx < a.B + a.N) {
+        const int64_t j = gidx - a.B;
+        float* crow = a.C + static_cast<int64_t>(a.w.negids[j]) * D;
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+            const int e = lg + m * G;
+            float sum = 0.0f;
+#pragma unroll
+            for (int s = 0; s < kSplit; ++s) sum += a.w.dCp[(static_cast<int64_t>(s) * a.N + j) * D + e];
+            unsafeAtomicAdd(crow + e, a.lr * sum);
+        }
+    }
+}
+
+template <int D>
+hipError_t run_shared(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t B, int32_t N, float lr,
+                      float neg_scale, uint64_t batch_index, const SharedWs& w, int32_t* neg_out, double* loss,
+                      hipStream_t st)
+{
+    constexpr int G = D / 8;
+    constexpr int GROUPS = 256 / G;
+    StageArgs sa{};
+    sa.X = reinterpret_cast<const float4*>(t->vertex); sa.C = reinterpret_cast<const float4*>(t->context);
+    sa.pairs = reinterpret_cast<const int2*>(pairs_dev); sa.B = B; sa.Bp = w.Bp; sa.N = N; sa.lr = lr;
+    sa.batch_index = batch_index; sa.k0 = static_cast<uint32_t>(t->seed); sa.k1 = static_cast<uint32_t>(t->seed >> 32);
+    sa.alias = al->table; sa.alias_n = static_cast<uint64_t>(al->n); sa.alias_base = al->base;
+    sa.w = w; sa.neg_out = neg_out; sa.loss = loss;
+    hipLaunchKernelGGL(stage_kernel<D>, dim3(static_cast<unsigned>((w.Bp + N + GROUPS - 1) / GROUPS)), dim3(256), 0, st, sa);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+
+    ScoresArgs ca{};
+    ca.w = w; ca.B = B; ca.N = N; ca.neg_scale = neg_scale; ca.loss = loss;
+    const size_t lds_bytes = (static_cast<size_t>(kRowTile + kNegChunk) * (D + 8) + static_cast<size_t>(D + kRowTile) * (kNegChunk + 8)) * 2;
+    // more than the default 64 KB of dynamic LDS (gfx950 has 160 KB per CU)
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(scores_kernel<D>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            static_cast<int>(lds_bytes));
+    if (e != hipSuccess) return e;
+    const bool timed = t->profile_every > 0 && t->batches_done % static_cast<uint64_t>(t->profile_every) == 0 &&
+                       t->ev_used < t->ev_start.size();
+    if (timed) {
+        e = hipEventRecord(t->ev_start[t->ev_used], st);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(scores_kernel<D>, dim3(static_cast<unsigned>(w.Bp / kRowTile)), dim3(256), lds_bytes, st, ca);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (timed) {
+        e = hipEventRecord(t->ev_stop[t->ev_used], st);
+        if (e != hipSuccess) return e;
+        t->ev_used += 1;
+    }
+    t->batches_done += 1;
+
+    DctxArgs da{};
+    da.w = w; da.N = N; da.D = D;
+    hipLaunchKernelGGL(dctx_kernel, dim3(N / 128, D / 64, kSplit), dim3(256), 0, st, da);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+
+    UpdateArgs ua{};
+    ua.X = t->vertex; ua.C = t->context; ua.pairs = sa.pairs; ua.B = B; ua.N = N; ua.lr = lr; ua.w = w;
+    hipLaunchKernelGGL(update_shared_kernel<D>, dim3(static_cast<unsigned>((B + N + GROUPS - 1) / GROUPS)), dim3(256), 0, st, ua);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t ne_shared_workspace_bytes(int32_t dim, int64_t B, int32_t N)
+{
+    SharedWs w;
+    if (!shared_layout(dim, B, N, nullptr, &w)) return 0;
+    return w.total;
+}
+
+ne_status ne_train_batch_shared(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t B, int32_t N,
+                                float lr, float neg_scale, uint64_t batch_index, void* workspace_dev,
+                                size_t workspace_bytes, int32_t* neg_out_dev, double* loss_sum_dev, void* hip_stream)
+{
+    if (!t || !al) return fail(NE_ERR_ARG, "tables or alias handle is NULL");
+    if (B < 0) return fail(NE_ERR_ARG, "B is negative");
+    if (B == 0) return NE_OK;
+    if (!pairs_dev || !aligned(pairs_dev, 8)) return fail(NE_ERR_ARG, "pairs_dev is NULL or not 8-byte aligned");
+    if (!std::isfinite(lr) || !std::isfinite(neg_scale)) return fail(NE_ERR_ARG, "lr or neg_scale is not finite");
+    if (al->base < 0 || al->base + al->n > t->num_nodes)
+        return fail(NE_ERR_STATE, "alias id range [base, base+n) is not inside the tables' [0, num_nodes)");
+    SharedWs w;
+    if (!shared_layout(t->dim, B, N, static_cast<char*>(workspace_dev), &w))
+        return fail(NE_ERR_ARG, "shared-negative mode needs dim in {64, 128, 256}, 1 <= B <= 2^20, N a multiple of 128 in [128, 65536]");
+    if (!workspace_dev || !aligned(workspace_dev, 256) || workspace_bytes < w.total)
+        return fail(NE_ERR_ARG, "workspace_dev is NULL, not 256-byte aligned, or smaller than ne_shared_workspace_bytes()");
+    if (loss_sum_dev && !aligned(loss_sum_dev, 8)) return fail(NE_ERR_ARG, "loss_sum_dev is misaligned");
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = hipErrorInvalidValue;
+    switch (t->dim) {
+        case 64: e = run_shared<64>(t, al, pairs_dev, B, N, lr, neg_scale, batch_index, w, neg_out_dev, loss_sum_dev, st); break;
+        case 128: e = run_shared<128>(t, al, pairs_dev, B, N, lr, neg_scale, batch_index, w, neg_out_dev, loss_sum_dev, st); break;
+        case 256: e = run_shared<256>(t, al, pairs_dev, B, N, lr, neg_scale, batch_index, w, neg_out_dev, loss_sum_dev, st); break;
+        default: break;
+    }
+    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("shared-negative launch: ") + hipGetErrorString(e));
+    return NE_OK;
+}
+
+}  // extern "C"
