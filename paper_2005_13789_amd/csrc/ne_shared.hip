@@ -13,7 +13,7 @@
 // Four kernels per batch:
 //   stage   gathers and rounds the rows, draws the N negatives, does the positive pairs in fp32 and
 //           stages their deltas; the tables are only read.
-//   scores  one workgroup per 64 pairs: S tile by tile on MFMA, sigmoid in registers, G to LDS (and
+//   scores  one workgroup per 64 pairs and share of the negatives: S tile by tile on MFMA, sigmoid in registers, G to LDS (and
 //           transposed to memory for the dC product), dX accumulated on MFMA over all N negatives.
 //   dctx    dC = G^T . Xq on MFMA, split over the batch dimension into partial sums.
 //   update  adds every staged delta to the tables with fp32 atomics (consecutive dwords per lane
@@ -26,11 +26,14 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kRowTile = 64;     // pairs per workgroup in the scores kernel
+constexpr int kRowTile = 128;    // pairs per workgroup in the scores kernel
+constexpr int kScoreThreads = 512;  // 8 wavefronts: two per SIMD, so that one's LDS traffic overlaps the other's MFMAs
 constexpr int kNegChunk = 64;    // negatives per LDS chunk in the scores kernel
-constexpr int kSplit = 8;        // partial sums of the dC product
-constexpr int kBatchPad = 128;   // the padded batch is a multiple of this
+constexpr int kSplit = 16;       // partial sums of the dC product
+constexpr int kNegSplit = 4;     // at most this many workgroups per row tile in the scores kernel, each taking a share of the negatives
+constexpr int kBatchPad = 1024;  // the padded batch is a multiple of this (kSplit shares of whole 64-pair steps)
 
 __device__ __forceinline__ uint16_t to_bf16(float x)
 {
@@ -38,6 +41,9 @@ __device__ __forceinline__ uint16_t to_bf16(float x)
     u += 0x7FFFu + ((u >> 16) & 1u);   // round to nearest even
     return static_cast<uint16_t>(u >> 16);
 }
+
+// sigmoid from the hardware exp2 and reciprocal (about 1 ulp each): the result is rounded to bf16 anyway
+__device__ __forceinline__ float fast_sigmoidf(float z) { return __frcp_rn(1.0f + __expf(-z)); }
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -49,7 +55,7 @@ struct SharedWs {
     uint16_t* GT;    // [N][Bp]   bf16 coefficients, transposed
     float* dxp;      // [Bp][d]   lr * g0 * c_ctx          (positive pair, source side)
     float* uctx;     // [Bp][d]   lr * g0 * x              (positive pair, context side)
-    float* dXn;      // [Bp][d]   G . Cq
+    float* dXn;      // [kNegSplit][Bp][d]   partial sums of G . Cq
     float* dCp;      // [kSplit][N][d] partial sums of G^T . Xq
     int32_t* negids; // [N]
     int64_t Bp;
@@ -73,7 +79,7 @@ bool shared_layout(int32_t dim, int64_t B, int32_t N, char* base, SharedWs* w)
     w->GT = reinterpret_cast<uint16_t*>(take(n * Bp * 2));
     w->dxp = reinterpret_cast<float*>(take(Bp * d * 4));
     w->uctx = reinterpret_cast<float*>(take(Bp * d * 4));
-    w->dXn = reinterpret_cast<float*>(take(Bp * d * 4));
+    w->dXn = reinterpret_cast<float*>(take(static_cast<size_t>(kNegSplit) * Bp * d * 4));
     w->dCp = reinterpret_cast<float*>(take(static_cast<size_t>(kSplit) * n * d * 4));
     w->negids = reinterpret_cast<int32_t*>(take(n * 4));
     w->total = off;
@@ -172,8 +178,8 @@ __global__ __launch_bounds__(256) void stage_kernel(StageArgs a)
 }
 
 // ---------------------------------------------------------------------------------------------
-// scores kernel: one workgroup (4 wavefronts) per 64 pairs.
-//   wavefront w: row half rh = w & 1 (32 pairs); column half ch = w >> 1
+// scores kernel: one workgroup (8 wavefronts) per 128 pairs and share of the negatives.
+//   wavefront w: row quarter rh = w & 3 (32 pairs); column half ch = w >> 2
 //   S tile   : pairs rh*32.. x negatives ch*32.. of the current 64-negative chunk   (1 MFMA tile)
 //   dX tiles : pairs rh*32.. x columns ch*D/2 .. ch*D/2 + D/2                        (D/64 tiles)
 // MFMA 32x32x16 operand layout (checked on hardware): lane l supplies row/column l%32 and the 8
@@ -189,30 +195,30 @@ struct ScoresArgs {
 };
 
 template <int D>
-__global__ __launch_bounds__(256) void scores_kernel(ScoresArgs a)
+__global__ __launch_bounds__(kScoreThreads) void scores_kernel(ScoresArgs a)
 {
     constexpr int XP = D + 8;            // pitch of Xs and Cs rows (bf16)
     constexpr int TP = kNegChunk + 8;    // pitch of CTs and Gs rows
     constexpr int DT = D / 64;           // dX tiles per wavefront
     extern __shared__ uint16_t lds[];
-    uint16_t* Xs = lds;                              // [64][XP]
+    uint16_t* Xs = lds;                              // [128][XP]
     uint16_t* Cs = Xs + kRowTile * XP;               // [64][XP]
     uint16_t* CTs = Cs + kNegChunk * XP;             // [D][TP]
-    uint16_t* Gs = CTs + D * TP;                     // [64][TP]
+    uint16_t* Gs = CTs + D * TP;                     // [128][TP]
     const int tid = threadIdx.x;
     const int l = tid & 63, w = tid >> 6;
-    const int rh = w & 1, ch = w >> 1;
+    const int rh = w & 3, ch = w >> 2;   // 32-pair quarter, half of the chunk / of the columns
     const int64_t b0 = static_cast<int64_t>(blockIdx.x) * kRowTile;
     const int64_t Bp = a.w.Bp;
 
-    // the 64 source rows of this workgroup
-    for (int c = tid; c < kRowTile * (D / 8); c += 256) {
+    // the source rows of this workgroup
+    for (int c = tid; c < kRowTile * (D / 8); c += kScoreThreads) {
         const int r = c / (D / 8), q = c % (D / 8);
         *reinterpret_cast<uint4*>(Xs + r * XP + q * 8) = *reinterpret_cast<const uint4*>(a.w.Xq + (b0 + r) * D + q * 8);
     }
     __syncthreads();
     // by-product: the transposed copy the dC product reads
-    for (int col = tid; col < D; col += 256) {
+    for (int col = tid; col < D && blockIdx.y == 0; col += kScoreThreads) {
         uint16_t* out = a.w.XqT + static_cast<int64_t>(col) * Bp + b0;
 #pragma unroll
         for (int r0 = 0; r0 < kRowTile; r0 += 8) {
@@ -231,19 +237,40 @@ __global__ __launch_bounds__(256) void scores_kernel(ScoresArgs a)
         for (int i = 0; i < 16; ++i) acc_dx[t][i] = 0.0f;
     float loss = 0.0f;
 
-    for (int n0 = 0; n0 < a.N; n0 += kNegChunk) {
-        // this chunk's negative rows, and their transpose
-        for (int c = tid; c < kNegChunk * (D / 8); c += 256) {
-            const int r = c / (D / 8), q = c % (D / 8);
-            *reinterpret_cast<uint4*>(Cs + r * XP + q * 8) =
-                *reinterpret_cast<const uint4*>(a.w.Cq + static_cast<int64_t>(n0 + r) * D + q * 8);
-        }
-        for (int c = tid; c < D * (kNegChunk / 8); c += 256) {
-            const int r = c / (kNegChunk / 8), q = c % (kNegChunk / 8);
-            *reinterpret_cast<uint4*>(CTs + r * TP + q * 8) =
-                *reinterpret_cast<const uint4*>(a.w.CqT + static_cast<int64_t>(r) * a.N + n0 + q * 8);
+    // this workgroup's share of the negatives, in chunks of 64; the next chunk's rows travel from
+    // memory into registers while the current one is being used
+    constexpr int CPT = kNegChunk * (D / 8) / kScoreThreads;   // 16-byte pieces of Cs per thread (= of CTs)
+    const int n_share = a.N / static_cast<int>(gridDim.y);
+    const int n_begin = blockIdx.y * n_share, n_end = n_begin + n_share;
+    u32x4 pc[CPT], pt[CPT];
+    // piece c of the chunk: Cs row c / (D/8), 16-byte column c % (D/8); CTs row c / 8, column c % 8
+    const uint16_t* src_c[CPT];
+    const uint16_t* src_t[CPT];
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+        const int c = tid + i * kScoreThreads;
+        src_c[i] = a.w.Cq + static_cast<int64_t>(n_begin + c / (D / 8)) * D + (c % (D / 8)) * 8;
+        src_t[i] = a.w.CqT + static_cast<int64_t>(c / (kNegChunk / 8)) * a.N + n_begin + (c % (kNegChunk / 8)) * 8;
+        pc[i] = *reinterpret_cast<const u32x4*>(src_c[i]);
+        pt[i] = *reinterpret_cast<const u32x4*>(src_t[i]);
+    }
+    for (int n0 = n_begin; n0 < n_end; n0 += kNegChunk) {
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+            const int c = tid + i * kScoreThreads;
+            *reinterpret_cast<u32x4*>(Cs + (c / (D / 8)) * XP + (c % (D / 8)) * 8) = pc[i];
+            *reinterpret_cast<u32x4*>(CTs + (c / (kNegChunk / 8)) * TP + (c % (kNegChunk / 8)) * 8) = pt[i];
         }
         __syncthreads();
+        if (n0 + kNegChunk < n_end) {
+#pragma unroll
+            for (int i = 0; i < CPT; ++i) {
+                src_c[i] += kNegChunk * D;
+                src_t[i] += kNegChunk;
+                pc[i] = *reinterpret_cast<const u32x4*>(src_c[i]);
+                pt[i] = *reinterpret_cast<const u32x4*>(src_t[i]);
+            }
+        }
 
         // S = Xq . Cq^T for 32 pairs x 32 negatives
         f32x16 s;
@@ -251,7 +278,7 @@ __global__ __launch_bounds__(256) void scores_kernel(ScoresArgs a)
         for (int i = 0; i < 16; ++i) s[i] = 0.0f;
         const uint16_t* xa = Xs + (rh * 32 + (l & 31)) * XP + (l >> 5) * 8;
         const uint16_t* cb = Cs + (ch * 32 + (l & 31)) * XP + (l >> 5) * 8;
-#pragma unroll 4
+#pragma unroll
         for (int k0 = 0; k0 < D; k0 += 16) {
             const bf16x8 av = as_bf16x8(*reinterpret_cast<const uint4*>(xa + k0));
             const bf16x8 bv = as_bf16x8(*reinterpret_cast<const uint4*>(cb + k0));
@@ -263,15 +290,15 @@ __global__ __launch_bounds__(256) void scores_kernel(ScoresArgs a)
             const int row = rh * 32 + (i >> 2) * 8 + (l >> 5) * 4 + (i & 3);
             const int col = ch * 32 + (l & 31);
             const bool valid = b0 + row < a.B;
-            const float g = valid ? -a.neg_scale * sigmoidf(s[i]) : 0.0f;
+            const float g = valid ? -a.neg_scale * fast_sigmoidf(s[i]) : 0.0f;
             if (a.loss && valid) loss += a.neg_scale * softplusf(s[i]);
             Gs[row * TP + col] = to_bf16(g);
         }
         __syncthreads();
 
-        // G^T to memory: 64 negatives x 64 pairs, 128 contiguous bytes per negative
+        // G^T to memory: 64 negatives x 128 pairs, 256 contiguous bytes per negative
         {
-            const int neg = tid >> 2, part = tid & 3;
+            const int neg = tid >> 3, part = tid & 7;
             uint32_t p[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i)
@@ -295,64 +322,123 @@ __global__ __launch_bounds__(256) void scores_kernel(ScoresArgs a)
         __syncthreads();   // Cs, CTs, Gs are rewritten by the next chunk
     }
 
+    float* dxn = a.w.dXn + static_cast<int64_t>(blockIdx.y) * Bp * D;
 #pragma unroll
     for (int t = 0; t < DT; ++t)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int row = rh * 32 + (i >> 2) * 8 + (l >> 5) * 4 + (i & 3);
             const int col = ch * (D / 2) + t * 32 + (l & 31);
-            a.w.dXn[(b0 + row) * D + col] = acc_dx[t][i];
+            dxn[(b0 + row) * D + col] = acc_dx[t][i];
         }
     if (a.loss) {
-        __shared__ double sh[4];
+        __shared__ double sh[kScoreThreads / 64];
         for (int off = 32; off > 0; off >>= 1) loss += __shfl_xor(loss, off, 64);
         if (l == 0) sh[w] = static_cast<double>(loss);
         __syncthreads();
-        if (tid == 0) atomicAdd(a.loss, sh[0] + sh[1] + sh[2] + sh[3]);
+        if (tid == 0) {
+            double total = 0.0;
+            for (int i = 0; i < kScoreThreads / 64; ++i) total += sh[i];
+            atomicAdd(a.loss, total);
+        }
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// dctx kernel: dC = G^T . Xq.  Workgroup tile 128 negatives x 64 columns, one k-range of the batch
-// per blockIdx.z; wavefront w: negatives w*32.., two 32x32 tiles side by side.  Operands come
-// straight from memory (both are k-contiguous there and small enough to stay in L2).
+// dctx kernel: dC = G^T . Xq.  Workgroup tile 128 negatives x TD columns (TD = 64 or 128), one share
+// of the batch (the contraction index) per blockIdx.z.  Both operands are contraction-contiguous in
+// memory (GT [N][Bp], XqT [d][Bp]); 64 contraction steps at a time are staged through LDS so that
+// the four wavefronts share them (operand traffic, not arithmetic, bounds this product), with the
+// next stage travelling into registers meanwhile.  Wavefront w: 64 negatives (w & 1) x TD/2 columns
+// (w >> 1).
 // ---------------------------------------------------------------------------------------------
 struct DctxArgs {
     SharedWs w;
     int32_t N, D;
 };
 
+template <int TD>
 __global__ __launch_bounds__(256) void dctx_kernel(DctxArgs a)
 {
-    const int l = threadIdx.x & 63, w = threadIdx.x >> 6;
+    constexpr int KP = 64 + 8;        // LDS pitch (bf16)
+    constexpr int BT = TD / 64;       // column tiles per wavefront
+    constexpr int BPT = TD * 8 / 256; // 16-byte pieces of the column operand per thread
+    __shared__ uint16_t As[128 * KP];
+    __shared__ uint16_t Bs[TD * KP];
+    const int tid = threadIdx.x, l = tid & 63, w = tid >> 6;
+    const int wr = w & 1, wc = w >> 1;
     const int64_t Bp = a.w.Bp;
-    const int64_t kc = Bp / kSplit;
+    const int kc = static_cast<int>(Bp / kSplit);
     const int64_t kbeg = static_cast<int64_t>(blockIdx.z) * kc;
-    const int n0 = blockIdx.x * 128 + w * 32;
-    const int d0 = blockIdx.y * 64;
-    f32x16 acc[2];
+    const int n0 = blockIdx.x * 128, d0 = blockIdx.y * TD;
+    f32x16 acc[2][BT];
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int r = 0; r < 2; ++r)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[t][i] = 0.0f;
-    const uint16_t* ga = a.w.GT + static_cast<int64_t>(n0 + (l & 31)) * Bp + kbeg + (l >> 5) * 8;
-    const uint16_t* xb0 = a.w.XqT + static_cast<int64_t>(d0 + (l & 31)) * Bp + kbeg + (l >> 5) * 8;
-    const uint16_t* xb1 = xb0 + 32 * Bp;
-#pragma unroll 4
-    for (int64_t k0 = 0; k0 < kc; k0 += 16) {
-        const bf16x8 av = as_bf16x8(*reinterpret_cast<const uint4*>(ga + k0));
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, as_bf16x8(*reinterpret_cast<const uint4*>(xb0 + k0)), acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, as_bf16x8(*reinterpret_cast<const uint4*>(xb1 + k0)), acc[1], 0, 0, 0);
+        for (int t = 0; t < BT; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[r][t][i] = 0.0f;
+
+    // piece c: row c / 8, 16-byte column c % 8
+    const uint16_t* src_a[4];
+    const uint16_t* src_b[BPT];
+    u32x4 pa[4], pb[BPT];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = tid + i * 256;
+        src_a[i] = a.w.GT + static_cast<int64_t>(n0 + c / 8) * Bp + kbeg + (c % 8) * 8;
+        pa[i] = *reinterpret_cast<const u32x4*>(src_a[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < BPT; ++i) {
+        const int c = tid + i * 256;
+        src_b[i] = a.w.XqT + static_cast<int64_t>(d0 + c / 8) * Bp + kbeg + (c % 8) * 8;
+        pb[i] = *reinterpret_cast<const u32x4*>(src_b[i]);
+    }
+    for (int k0 = 0; k0 < kc; k0 += 64) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int c = tid + i * 256;
+            *reinterpret_cast<u32x4*>(As + (c / 8) * KP + (c % 8) * 8) = pa[i];
+        }
+#pragma unroll
+        for (int i = 0; i < BPT; ++i) {
+            const int c = tid + i * 256;
+            *reinterpret_cast<u32x4*>(Bs + (c / 8) * KP + (c % 8) * 8) = pb[i];
+        }
+        __syncthreads();
+        if (k0 + 64 < kc) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { src_a[i] += 64; pa[i] = *reinterpret_cast<const u32x4*>(src_a[i]); }
+#pragma unroll
+            for (int i = 0; i < BPT; ++i) { src_b[i] += 64; pb[i] = *reinterpret_cast<const u32x4*>(src_b[i]); }
+        }
+        const uint16_t* ar = As + (wr * 64 + (l & 31)) * KP + (l >> 5) * 8;
+        const uint16_t* br = Bs + (wc * (TD / 2) + (l & 31)) * KP + (l >> 5) * 8;
+#pragma unroll
+        for (int kk = 0; kk < 64; kk += 16) {
+            const bf16x8 a0 = as_bf16x8(*reinterpret_cast<const uint4*>(ar + kk));
+            const bf16x8 a1 = as_bf16x8(*reinterpret_cast<const uint4*>(ar + 32 * KP + kk));
+#pragma unroll
+            for (int t = 0; t < BT; ++t) {
+                const bf16x8 bv = as_bf16x8(*reinterpret_cast<const uint4*>(br + t * 32 * KP + kk));
+                acc[0][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bv, acc[0][t], 0, 0, 0);
+                acc[1][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bv, acc[1][t], 0, 0, 0);
+            }
+        }
+        __syncthreads();
     }
     float* out = a.w.dCp + static_cast<int64_t>(blockIdx.z) * a.N * a.D;
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int r = 0; r < 2; ++r)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int row = n0 + (i >> 2) * 8 + (l >> 5) * 4 + (i & 3);
-            const int col = d0 + t * 32 + (l & 31);
-            out[static_cast<int64_t>(row) * a.D + col] = acc[t][i];
-        }
+        for (int t = 0; t < BT; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int row = n0 + wr * 64 + r * 32 + (i >> 2) * 8 + (l >> 5) * 4 + (i & 3);
+                const int col = d0 + wc * (TD / 2) + t * 32 + (l & 31);
+                out[static_cast<int64_t>(row) * a.D + col] = acc[r][t][i];
+            }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -366,6 +452,7 @@ struct UpdateArgs {
     int64_t B;
     int32_t N;
     float lr;
+    int32_t neg_split;   // partial sums of dXn that were written
     SharedWs w;
 };
 
@@ -382,11 +469,16 @@ __global__ __launch_bounds__(256) void update_shared_kernel(UpdateArgs a)
         float* crow = a.C + static_cast<int64_t>(pr.y) * D;
         const float* dxp = a.w.dxp + gidx * D;
         const float* dxn = a.w.dXn + gidx * D;
+        const int64_t part = a.w.Bp * D;
         const float* uctx = a.w.uctx + gidx * D;
 #pragma unroll
         for (int m = 0; m < 8; ++m) {
             const int e = lg + m * G;
-            unsafeAtomicAdd(xrow + e, fmaf(a.lr, dxn[e], dxp[e]));
+            float neg_part = 0.0f;
+#pragma unroll
+            for (int s = 0; s < kNegSplit; ++s)
+                if (s < a.neg_split) neg_part += dxn[s * part + e];
+            unsafeAtomicAdd(xrow + e, fmaf(a.lr, neg_part, dxp[e]));
             unsafeAtomicAdd(crow + e, uctx[e]);
         }
     } else if (gidx < a.B + a.N) {
@@ -420,6 +512,8 @@ hipError_t run_shared(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
+    // shares of the negatives must be whole 64-negative chunks
+    const unsigned neg_split = (N % (kNegSplit * kNegChunk) == 0) ? kNegSplit : 2;
     ScoresArgs ca{};
     ca.w = w; ca.B = B; ca.N = N; ca.neg_scale = neg_scale; ca.loss = loss;
     const size_t lds_bytes = (static_cast<size_t>(kRowTile + kNegChunk) * (D + 8) + static_cast<size_t>(D + kRowTile) * (kNegChunk + 8)) * 2;
@@ -433,7 +527,7 @@ hipError_t run_shared(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev
         e = hipEventRecord(t->ev_start[t->ev_used], st);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(scores_kernel<D>, dim3(static_cast<unsigned>(w.Bp / kRowTile)), dim3(256), lds_bytes, st, ca);
+    hipLaunchKernelGGL(scores_kernel<D>, dim3(static_cast<unsigned>(w.Bp / kRowTile), neg_split), dim3(kScoreThreads), lds_bytes, st, ca);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (timed) {
@@ -445,12 +539,15 @@ hipError_t run_shared(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev
 
     DctxArgs da{};
     da.w = w; da.N = N; da.D = D;
-    hipLaunchKernelGGL(dctx_kernel, dim3(N / 128, D / 64, kSplit), dim3(256), 0, st, da);
+    if (D >= 128)
+        hipLaunchKernelGGL(dctx_kernel<128>, dim3(N / 128, D / 128, kSplit), dim3(256), 0, st, da);
+    else
+        hipLaunchKernelGGL(dctx_kernel<64>, dim3(N / 128, 1, kSplit), dim3(256), 0, st, da);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
 
     UpdateArgs ua{};
-    ua.X = t->vertex; ua.C = t->context; ua.pairs = sa.pairs; ua.B = B; ua.N = N; ua.lr = lr; ua.w = w;
+    ua.X = t->vertex; ua.C = t->context; ua.pairs = sa.pairs; ua.B = B; ua.N = N; ua.lr = lr; ua.neg_split = static_cast<int32_t>(neg_split); ua.w = w;
     hipLaunchKernelGGL(update_shared_kernel<D>, dim3(static_cast<unsigned>((B + N + GROUPS - 1) / GROUPS)), dim3(256), 0, st, ua);
     return hipGetLastError();
 }
