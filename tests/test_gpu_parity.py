@@ -242,3 +242,68 @@ def test_train_block_matches_oracle_and_single_batches():
         oracle.train_batch(Xo, Co, np.ascontiguousarray(ids[sl]), neg_o, lrs[i])
     Xg, Cg = m.host_tables()
     assert rowwise_rel_err(Xg, Xo) <= 1e-3 and rowwise_rel_err(Cg, Co) <= 1e-3
+
+
+@pytest.mark.parametrize("V,d,K,B,n_pairs", [(3000, 512, 10, 512, 5 * 512 + 100), (2500, 64, 0, 1024, 4 * 1024), (800, 128, 62, 64, 5 * 64 + 1),
+                                             (50, 128, 5, 2048, 6 * 2048)])
+def test_train_block_shapes(V, d, K, B, n_pairs):
+    """ne_train_block over other lane-group shapes, K = 0, the largest K, and a table so small that
+    almost every row is named many times per batch (the shared-row path carries nearly everything)."""
+    say(f"train_block V={V} d={d} K={K} B={B} n_pairs={n_pairs}")
+    seed = 21
+    rng = np.random.default_rng(V + d)
+    deg = (rng.pareto(1.0, V) * 2).astype(np.uint32) + 1
+    X0 = rng.normal(0, 1.0 / np.sqrt(d), (V, d)).astype(np.float32)
+    C0 = rng.normal(0, 1.0 / np.sqrt(d), (V, d)).astype(np.float32)
+    ids = rng.integers(0, V, (n_pairs, 2)).astype(np.int32)
+    nb = -(-n_pairs // B)
+    lrs = [0.02] * nb
+    m = GpuModel(V, d, seed, deg if K > 0 else None, K, B, X=X0, C=C0)
+    ne.ne_train_block(m.tables, m.alias, torch.from_numpy(ids).cuda(), B, K, lrs, 5)
+    Xg, Cg = m.host_tables()
+    Xo, Co = X0.copy(), C0.copy()
+    if K > 0:
+        thr, alias, _ = oracle.build_alias(deg)
+    for i in range(nb):
+        sl = slice(i * B, min((i + 1) * B, n_pairs))
+        neg_o = (oracle.sample_negatives(seed, 5 + i * B, sl.stop - sl.start, K, thr, alias) if K > 0
+                 else np.zeros((sl.stop - sl.start, 0), np.int32))
+        oracle.train_batch(Xo, Co, np.ascontiguousarray(ids[sl]), neg_o, lrs[i])
+    ex, ec = rowwise_rel_err(Xg, Xo), rowwise_rel_err(Cg, Co)
+    say(f"  rowwise err X {ex:.2e} C {ec:.2e}")
+    assert ex <= 1e-3 and ec <= 1e-3
+
+
+def test_long_run_keeps_hash_state_clean():
+    """400 batches on one handle, alternating ne_train_block runs of different lengths and batch sizes
+    with single ne_train_batch calls: any stale hash position or slot would show up as drift."""
+    say("long run, 400 batches")
+    V, d, K, seed = 4000, 64, 5, 9
+    rng = np.random.default_rng(5)
+    deg = (rng.pareto(1.0, V) * 2).astype(np.uint32) + 1
+    X0 = rng.normal(0, 0.1, (V, d)).astype(np.float32)
+    C0 = rng.normal(0, 0.1, (V, d)).astype(np.float32)
+    m = GpuModel(V, d, seed, deg, K, 1024, X=X0, C=C0)
+    thr, alias, _ = oracle.build_alias(deg)
+    Xo, Co = X0.copy(), C0.copy()
+    done, base = 0, 0
+    while done < 400:
+        B = int(rng.choice([1024, 512, 333]))
+        nb = int(rng.integers(1, 9))
+        n_pairs = nb * B - int(rng.integers(0, B // 2))
+        ids = np.minimum((rng.pareto(0.9, (n_pairs, 2)) * V / 40).astype(np.int64), V - 1).astype(np.int32)
+        pd = torch.from_numpy(ids).cuda()
+        if nb == 1:
+            ne.ne_train_batch(m.tables, m.alias, pd, K, 0.01, base)
+        else:
+            ne.ne_train_block(m.tables, m.alias, pd, B, K, [0.01] * nb, base)
+        for i in range(-(-n_pairs // B) if nb > 1 else 1):
+            sl = slice(i * B, min((i + 1) * B, n_pairs)) if nb > 1 else slice(0, n_pairs)
+            neg_o = oracle.sample_negatives(seed, base + sl.start, sl.stop - sl.start, K, thr, alias)
+            oracle.train_batch(Xo, Co, np.ascontiguousarray(ids[sl]), neg_o, 0.01)
+        base += n_pairs
+        done += nb
+    Xg, Cg = m.host_tables()
+    ex, ec = rowwise_rel_err(Xg, Xo), rowwise_rel_err(Cg, Co)
+    say(f"  after {done} batches: rowwise err X {ex:.2e} C {ec:.2e}")
+    assert ex <= 2e-3 and ec <= 2e-3
