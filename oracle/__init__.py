@@ -54,6 +54,8 @@ def _load():
     lib.oracle_train_batch_shared.argtypes = [p, p, c.c_int64, c.c_int32, p, c.c_int64, p, c.c_int32, c.c_float,
                                               c.c_float, c.c_int32, c.POINTER(c.c_double)]
     lib.oracle_train_batch_shared.restype = c.c_int
+    lib.oracle_train_sequential.argtypes = [p, p, c.c_int64, c.c_int32, p, c.c_int64, c.c_int32, c.c_float, p]
+    lib.oracle_train_sequential.restype = c.c_int
     lib.oracle_eval_loss.argtypes = [p, p, c.c_int64, c.c_int32, p, c.c_int64, c.c_int32, p]
     lib.oracle_eval_loss.restype = c.c_double
     _lib = lib
@@ -173,3 +175,18 @@ def train_batch_shared(X: np.ndarray, C: np.ndarray, pairs: np.ndarray, negs: np
     if rc != 0:
         raise ValueError(f"oracle_train_batch_shared failed ({rc})")
     return loss.value
+
+
+def train_sequential(X: np.ndarray, C: np.ndarray, pairs: np.ndarray, neg: np.ndarray, lr: float) -> None:
+    """Per-sample SGD in the order of pairs, in place: each sample sees what the ones before it left."""
+    _chk(X, np.float32, "X")
+    _chk(C, np.float32, "C")
+    _chk(pairs, np.int32, "pairs")
+    _chk(neg, np.int32, "neg")
+    V, d = X.shape
+    B = pairs.shape[0]
+    K = neg.shape[1]
+    assert neg.shape == (B, K)
+    rc = _load().oracle_train_sequential(_ptr(X), _ptr(C), V, d, _ptr(pairs), B, K, np.float32(lr), _ptr(neg))
+    if rc != 0:
+        raise ValueError(f"oracle_train_sequential failed ({rc})")

@@ -376,3 +376,46 @@ int oracle_train_batch_shared(float* X, float* C, int64_t V, int32_t d, const in
     dm_free(&DX); dm_free(&DC);
     return 0;
 }
+
+/* ------------------------------------------------------------------------- */
+/* Per-sample ("asynchronous") training: the loop of Algorithm 1 taken         */
+/* literally, one edge sample after the other, each seeing the tables as the   */
+/* samples before it left them.  Within one sample the K+1 Train calls use the */
+/* source row as it was when the sample started and the source row is updated  */
+/* once with the summed gradient (the word2vec convention); context rows are   */
+/* updated after the sample's scores are formed.  This is the reference for    */
+/* the GPU's unsynchronised mode, which is compared statistically (loss curve) */
+/* and, on batches in which no row is named twice, element by element.         */
+/* ------------------------------------------------------------------------- */
+int oracle_train_sequential(float* X, float* C, int64_t V, int32_t d, const int32_t* pairs, int64_t B,
+                            int32_t K, float lr_f, const int32_t* neg)
+{
+    const double lr = (double)lr_f;
+    double* dx = (double*)malloc((size_t)d * sizeof(double));
+    double* g = (double*)malloc((size_t)(K + 1) * sizeof(double));
+    double* xs = (double*)malloc((size_t)d * sizeof(double));
+    if (!dx || !g || !xs) { free(dx); free(g); free(xs); return -2; }
+    for (int64_t b = 0; b < B; ++b) {
+        const int64_t src = pairs[2 * b];
+        if (src < 0 || src >= V) { free(dx); free(g); free(xs); return -1; }
+        float* x = X + src * (int64_t)d;
+        for (int32_t i = 0; i < d; ++i) { dx[i] = 0.0; xs[i] = (double)x[i]; }
+        for (int32_t j = 0; j <= K; ++j) {
+            const int64_t id = (j == 0) ? pairs[2 * b + 1] : neg[b * K + (j - 1)];
+            if (id < 0 || id >= V) { free(dx); free(g); free(xs); return -1; }
+            const float* c = C + id * (int64_t)d;
+            double s = 0.0;
+            for (int32_t i = 0; i < d; ++i) s += xs[i] * (double)c[i];
+            g[j] = (j == 0) ? 1.0 - sigmoid(s) : -sigmoid(s);
+            for (int32_t i = 0; i < d; ++i) dx[i] += lr * g[j] * (double)c[i];
+        }
+        for (int32_t j = 0; j <= K; ++j) {
+            const int64_t id = (j == 0) ? pairs[2 * b + 1] : neg[b * K + (j - 1)];
+            float* c = C + id * (int64_t)d;
+            for (int32_t i = 0; i < d; ++i) c[i] = (float)((double)c[i] + lr * g[j] * xs[i]);
+        }
+        for (int32_t i = 0; i < d; ++i) x[i] = (float)(xs[i] + dx[i]);
+    }
+    free(dx); free(g); free(xs);
+    return 0;
+}
