@@ -152,6 +152,20 @@ ne_status ne_train_batch_shared(ne_tables* tables, const ne_alias* alias, const 
                                 double* loss_sum_dev, void* hip_stream);
 
 /*
+ * Per-sample ("asynchronous") training: the same arithmetic as ne_train_batch, but every pair is
+ * trained on its own as in the loop of Algorithm 1, without waiting for the other pairs of the
+ * call: each pair reads its 2+K rows as they are at that moment and writes all of them back at once
+ * (old + delta, plain stores).  Pairs of one call run concurrently, so two pairs that name the same
+ * row race: one of the two updates may be lost, and a pair may read a row that another pair of the
+ * same call has already rewritten.  The result therefore depends on timing and is not reproducible
+ * bit for bit; it equals ne_train_batch exactly (up to fp32 rounding) only when no row is named
+ * twice in the call.  Needs no workspace.  Negatives, arguments and errors as for ne_train_batch.
+ */
+ne_status ne_train_batch_async(ne_tables* tables, const ne_alias* alias, const int32_t* pairs_dev,
+                               int64_t B, int32_t K, float lr, uint64_t sample_base,
+                               int32_t* neg_out_dev, void* hip_stream);
+
+/*
  * Loss of a batch at the current tables with the same negatives ne_train_batch would draw; nothing
  * is updated.  Adds  sum_b [ -log sigmoid(s_b0) - sum_k log sigmoid(-s_bk) ]  (fp32 terms, fp64 sum)
  * to *loss_sum_dev.

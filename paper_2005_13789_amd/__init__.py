@@ -26,7 +26,7 @@ NE_MAX_BATCH = 1 << 22
 
 EXPORTS = (
     "ne_create_tables", "ne_build_neg_alias", "ne_workspace_bytes", "ne_train_batch", "ne_train_block",
-    "ne_shared_workspace_bytes", "ne_train_batch_shared", "ne_eval_loss",
+    "ne_shared_workspace_bytes", "ne_train_batch_shared", "ne_train_batch_async", "ne_eval_loss",
     "ne_validate_pairs", "ne_profile_enable", "ne_profile_read", "ne_destroy_tables", "ne_destroy_alias", "ne_last_error",
 )
 
@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
     L.ne_train_batch_shared.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_float, c.c_float, c.c_uint64, vp,
                                         c.c_size_t, vp, vp, vp]
     L.ne_train_batch_shared.restype = c.c_int
+    L.ne_train_batch_async.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_float, c.c_uint64, vp, vp]
+    L.ne_train_batch_async.restype = c.c_int
     L.ne_eval_loss.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_uint64, vp, vp, vp]
     L.ne_eval_loss.restype = c.c_int
     L.ne_validate_pairs.argtypes = [vp, vp, c.c_int64, vp, vp]
@@ -202,6 +204,18 @@ def ne_train_block(tables: Tables, alias: Alias | None, pairs: torch.Tensor, B: 
         raise TypeError("neg_out needs n_pairs*K int32 elements")
     _check(lib().ne_train_block(tables.handle, alias.handle if alias else None, pp, n_pairs, B, K, arr, sample_base,
                                 np_, _stream_ptr(stream)))
+
+
+def ne_train_batch_async(tables: Tables, alias: Alias | None, pairs: torch.Tensor, K: int, lr: float,
+                         sample_base: int, neg_out: torch.Tensor | None = None, stream=None) -> None:
+    """Unsynchronised per-sample step on pairs int32 [B][2] (CUDA): rows named twice race."""
+    B = int(pairs.shape[0])
+    pp = _dev_ptr(pairs, torch.int32, "pairs")
+    np_ = _dev_ptr(neg_out, torch.int32, "neg_out")
+    if neg_out is not None and neg_out.numel() < B * K:
+        raise TypeError("neg_out needs B*K int32 elements")
+    _check(lib().ne_train_batch_async(tables.handle, alias.handle if alias else None, pp, B, K, lr, sample_base,
+                                      np_, _stream_ptr(stream)))
 
 
 def ne_shared_workspace_bytes(dim: int, B: int, N: int) -> int:

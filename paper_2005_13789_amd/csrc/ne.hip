@@ -508,6 +508,101 @@ __global__ __launch_bounds__(256) void loss_kernel(LossArgs a)
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// async kernel (ne_train_batch_async): per-sample training without synchronisation, the loop of
+// Algorithm 1 taken literally on a parallel machine.  One lane group per pair draws the negatives,
+// gathers the rows, scores, and writes every row back at once with plain stores (old + delta).  No
+// row is protected: two pairs that name the same row race, the later store wins, and a pair may read
+// a row another pair has just rewritten.  Every row costs exactly one read and one write.
+// ---------------------------------------------------------------------------------------------
+struct AsyncArgs {
+    float4* X;
+    float4* C;
+    const int2* pairs;
+    int64_t B;
+    int32_t K;
+    int32_t d4;
+    float lr;
+    uint64_t sample_base;
+    uint32_t k0, k1;
+    const uint2* alias;
+    uint64_t alias_n;
+    int32_t alias_base;
+    int32_t* neg_out;
+};
+
+template <int G, int NCH, int JB>
+__global__ __launch_bounds__(256) void async_kernel(AsyncArgs a)
+{
+    constexpr int GROUPS = 256 / G;
+    const int lg = threadIdx.x & (G - 1);
+    const int64_t b = static_cast<int64_t>(blockIdx.x) * GROUPS + (threadIdx.x / G);
+    if (b >= a.B) return;   // whole groups leave together; groups never communicate
+    const int K = a.K;
+    const int d4 = a.d4;
+    const int2 pr = a.pairs[b];
+
+    // lane lg owns context row j = lg of the pair: j = 0 the positive, j = 1..K negative j-1
+    int32_t id_mine = pr.y;
+    if (lg >= 1 && lg <= K) {
+        id_mine = draw_negative(a.sample_base + static_cast<uint64_t>(b), static_cast<uint32_t>(lg - 1), a.k0, a.k1,
+                                a.alias, a.alias_n, a.alias_base);
+        if (a.neg_out) a.neg_out[b * K + (lg - 1)] = id_mine;
+    }
+    float4* xrow = a.X + static_cast<int64_t>(pr.x) * d4;
+    float4 xr[NCH], dx[NCH];
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int ci = lg + i * G;
+        xr[i] = (ci < d4) ? xrow[ci] : make_float4(0.f, 0.f, 0.f, 0.f);
+        dx[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    for (int j0 = 0; j0 <= K; j0 += JB) {
+        float4 cr[JB][NCH];
+        float part[JB];
+        float4* crow[JB];
+#pragma unroll
+        for (int jj = 0; jj < JB; ++jj) {
+            const int j = j0 + jj;
+            const int32_t id = __shfl(id_mine, j <= K ? j : K, G);
+            crow[jj] = a.C + static_cast<int64_t>(id) * d4;
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) {
+                const int ci = lg + i * G;
+                cr[jj][i] = (j <= K && ci < d4) ? crow[jj][ci] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+#pragma unroll
+        for (int jj = 0; jj < JB; ++jj) {
+            float p = 0.0f;
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) p += dot4(xr[i], cr[jj][i]);
+            part[jj] = p;
+        }
+#pragma unroll
+        for (int jj = 0; jj < JB; ++jj) part[jj] = group_sum<G>(part[jj]);
+#pragma unroll
+        for (int jj = 0; jj < JB; ++jj) {
+            const int j = j0 + jj;
+            if (j <= K) {
+                const float sg = sigmoidf(part[jj]);
+                const float g = a.lr * (j == 0 ? 1.0f - sg : -sg);
+#pragma unroll
+                for (int i = 0; i < NCH; ++i) {
+                    const int ci = lg + i * G;
+                    dx[i] = axpy4(g, cr[jj][i], dx[i]);
+                    if (ci < d4) crow[jj][ci] = axpy4(g, xr[i], cr[jj][i]);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int ci = lg + i * G;
+        if (ci < d4) xrow[ci] = make_float4(xr[i].x + dx[i].x, xr[i].y + dx[i].y, xr[i].z + dx[i].z, xr[i].w + dx[i].w);
+    }
+}
+
 __global__ __launch_bounds__(256) void validate_pairs_kernel(const int32_t* __restrict__ ids, int64_t count,
                                                              int64_t num_nodes, unsigned long long* bad)
 {
@@ -560,6 +655,20 @@ hipError_t launch_loss(const Shape& s, const LossArgs& a, hipStream_t st)
 #define NE_CASE(G_, N_)                                                                          \
     if (s.G == G_ && s.NCH == N_) {                                                              \
         hipLaunchKernelGGL((loss_kernel<G_, N_, 6>), dim3(grid), dim3(256), 0, st, a);           \
+        return hipGetLastError();                                                                \
+    }
+    NE_FOR_EACH_SHAPE(NE_CASE)
+#undef NE_CASE
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_async(const Shape& s, const AsyncArgs& a, hipStream_t st)
+{
+    const int groups = 256 / s.G;
+    const unsigned grid = static_cast<unsigned>((a.B + groups - 1) / groups);
+#define NE_CASE(G_, N_)                                                                          \
+    if (s.G == G_ && s.NCH == N_) {                                                              \
+        hipLaunchKernelGGL((async_kernel<G_, N_, 6>), dim3(grid), dim3(256), 0, st, a);          \
         return hipGetLastError();                                                                \
     }
     NE_FOR_EACH_SHAPE(NE_CASE)
@@ -891,6 +1000,35 @@ ne_status ne_train_batch(ne_tables* t, const ne_alias* al, const int32_t* pairs_
         return check_batch_args(t, al, pairs_dev, B, K, &shape);
     }
     return ne_train_block(t, al, pairs_dev, B, B, K, &lr, sample_base, neg_out_dev, hip_stream);
+}
+
+ne_status ne_train_batch_async(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t B, int32_t K,
+                               float lr, uint64_t sample_base, int32_t* neg_out_dev, void* hip_stream)
+{
+    Shape shape;
+    ne_status rc = check_batch_args(t, al, pairs_dev, B, K, &shape);
+    if (rc != NE_OK) return rc;
+    if (!std::isfinite(lr)) return fail(NE_ERR_ARG, "lr is not finite");
+    if (B == 0) return NE_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    AsyncArgs aa{};
+    aa.X = reinterpret_cast<float4*>(t->vertex); aa.C = reinterpret_cast<float4*>(t->context);
+    aa.pairs = reinterpret_cast<const int2*>(pairs_dev);
+    aa.B = B; aa.K = K; aa.d4 = t->dim / 4; aa.lr = lr; aa.sample_base = sample_base;
+    aa.k0 = static_cast<uint32_t>(t->seed); aa.k1 = static_cast<uint32_t>(t->seed >> 32);
+    aa.alias = al ? al->table : nullptr; aa.alias_n = al ? static_cast<uint64_t>(al->n) : 1; aa.alias_base = al ? al->base : 0;
+    aa.neg_out = neg_out_dev;
+    const bool timed = t->profile_every > 0 && t->batches_done % static_cast<uint64_t>(t->profile_every) == 0 &&
+                       t->ev_used < t->ev_start.size();
+    if (timed) NE_HIP_CHECK(hipEventRecord(t->ev_start[t->ev_used], st));
+    hipError_t e = launch_async(shape, aa, st);
+    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("async launch: ") + hipGetErrorString(e));
+    if (timed) {
+        NE_HIP_CHECK(hipEventRecord(t->ev_stop[t->ev_used], st));
+        t->ev_used += 1;
+    }
+    t->batches_done += 1;
+    return NE_OK;
 }
 
 ne_status ne_eval_loss(const ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t B, int32_t K,
