@@ -33,7 +33,12 @@ def _load():
     if _lib is not None:
         return _lib
     build(force=False)
-    lib = ctypes.CDLL(_SO)
+    _lib = _bind(ctypes.CDLL(_SO))
+    return _lib
+
+
+def _bind(lib):
+    """Declare the C signatures on a loaded copy of the oracle library."""
     c = ctypes
     p = c.c_void_p
     lib.oracle_philox4x32_10.argtypes = [p, p, p]
@@ -58,7 +63,6 @@ def _load():
     lib.oracle_train_sequential.restype = c.c_int
     lib.oracle_eval_loss.argtypes = [p, p, c.c_int64, c.c_int32, p, c.c_int64, c.c_int32, p]
     lib.oracle_eval_loss.restype = c.c_double
-    _lib = lib
     return lib
 
 
