@@ -190,8 +190,10 @@ ne_status ne_validate_pairs(const ne_tables* tables, const int32_t* pairs_dev, i
  * on the stream immediately before and after its train kernel (the kernel that gathers the rows,
  * scores and writes them back; for ne_train_batch_shared: the scores kernel with the S and dX
  * products), for at most max_samples (<= 65536) calls; n = 0 switches it off.
- * ne_profile_read waits for the recorded events, stores the sum of the kernel durations in
- * milliseconds in *total_ms_host and their number in *samples_host (both host), and starts over.
+ * Two events are recorded back to back before the kernel; the gap between them is taken as the cost
+ * of recording and subtracted.  ne_profile_read waits for the recorded events, stores the sum of
+ * the kernel durations in milliseconds in *total_ms_host and their number in *samples_host (both
+ * host), and starts over.
  */
 ne_status ne_profile_enable(ne_tables* tables, int32_t every_n, int32_t max_samples);
 ne_status ne_profile_read(ne_tables* tables, double* total_ms_host, int64_t* samples_host);

@@ -804,6 +804,7 @@ ne_status ne_create_tables(ne_tables** out, int64_t num_nodes, int32_t dim, floa
 void ne_destroy_tables(ne_tables* t)
 {
     if (!t) return;
+    for (hipEvent_t e : t->ev_zero) (void)hipEventDestroy(e);
     for (hipEvent_t e : t->ev_start) (void)hipEventDestroy(e);
     for (hipEvent_t e : t->ev_stop) (void)hipEventDestroy(e);
     delete t;
@@ -816,13 +817,16 @@ ne_status ne_profile_enable(ne_tables* t, int32_t every_n, int32_t max_samples)
     t->profile_every = every_n;
     t->ev_used = 0;
     while (every_n > 0 && t->ev_start.size() < static_cast<size_t>(max_samples)) {
-        hipEvent_t a = nullptr, b = nullptr;
-        NE_HIP_CHECK(hipEventCreate(&a));
-        hipError_t e = hipEventCreate(&b);
+        hipEvent_t z = nullptr, a = nullptr, b = nullptr;
+        hipError_t e = hipEventCreate(&z);
+        if (e == hipSuccess) e = hipEventCreate(&a);
+        if (e == hipSuccess) e = hipEventCreate(&b);
         if (e != hipSuccess) {
-            (void)hipEventDestroy(a);
+            if (z) (void)hipEventDestroy(z);
+            if (a) (void)hipEventDestroy(a);
             return fail(NE_ERR_HIP, std::string("hipEventCreate: ") + hipGetErrorString(e));
         }
+        t->ev_zero.push_back(z);
         t->ev_start.push_back(a);
         t->ev_stop.push_back(b);
     }
@@ -835,9 +839,10 @@ ne_status ne_profile_read(ne_tables* t, double* total_ms_host, int64_t* samples_
     double total = 0.0;
     for (size_t i = 0; i < t->ev_used; ++i) {
         NE_HIP_CHECK(hipEventSynchronize(t->ev_stop[i]));
-        float ms = 0.0f;
+        float ms = 0.0f, overhead = 0.0f;
         NE_HIP_CHECK(hipEventElapsedTime(&ms, t->ev_start[i], t->ev_stop[i]));
-        total += static_cast<double>(ms);
+        NE_HIP_CHECK(hipEventElapsedTime(&overhead, t->ev_zero[i], t->ev_start[i]));
+        total += static_cast<double>(ms > overhead ? ms - overhead : 0.0f);
     }
     *total_ms_host = total;
     *samples_host = static_cast<int64_t>(t->ev_used);
@@ -966,15 +971,10 @@ ne_status ne_train_block(ne_tables* t, const ne_alias* al, const int32_t* pairs_
         ta.X = reinterpret_cast<float4*>(t->vertex); ta.C = reinterpret_cast<float4*>(t->context);
         ta.B = cur.refs / R; ta.K = K; ta.d4 = t->dim / 4; ta.lr = lr_host[i];
         ta.ids = ps.ids; ta.posbuf = ps.posbuf; ta.shared = ps.shared; ta.delta = w.delta;
-        const bool timed = t->profile_every > 0 && t->batches_done % static_cast<uint64_t>(t->profile_every) == 0 &&
-                           t->ev_used < t->ev_start.size();
-        if (timed) NE_HIP_CHECK(hipEventRecord(t->ev_start[t->ev_used], st));
+        const bool timed = profile_begin(t, st);
         e = launch_train(shape, ta, next, st);
         if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("train launch: ") + hipGetErrorString(e));
-        if (timed) {
-            NE_HIP_CHECK(hipEventRecord(t->ev_stop[t->ev_used], st));
-            t->ev_used += 1;
-        }
+        if (timed) profile_end(t, st);
 
         ApplyArgs aa{};
         aa.X = ta.X; aa.C = ta.C; aa.d4 = ta.d4; aa.delta = reinterpret_cast<float4*>(w.delta);
@@ -1018,15 +1018,10 @@ ne_status ne_train_batch_async(ne_tables* t, const ne_alias* al, const int32_t* 
     aa.k0 = static_cast<uint32_t>(t->seed); aa.k1 = static_cast<uint32_t>(t->seed >> 32);
     aa.alias = al ? al->table : nullptr; aa.alias_n = al ? static_cast<uint64_t>(al->n) : 1; aa.alias_base = al ? al->base : 0;
     aa.neg_out = neg_out_dev;
-    const bool timed = t->profile_every > 0 && t->batches_done % static_cast<uint64_t>(t->profile_every) == 0 &&
-                       t->ev_used < t->ev_start.size();
-    if (timed) NE_HIP_CHECK(hipEventRecord(t->ev_start[t->ev_used], st));
+    const bool timed = profile_begin(t, st);
     hipError_t e = launch_async(shape, aa, st);
     if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("async launch: ") + hipGetErrorString(e));
-    if (timed) {
-        NE_HIP_CHECK(hipEventRecord(t->ev_stop[t->ev_used], st));
-        t->ev_used += 1;
-    }
+    if (timed) profile_end(t, st);
     t->batches_done += 1;
     return NE_OK;
 }

@@ -57,7 +57,7 @@ struct ne_tables {
     uint64_t batches_done;
     // optional timing of the train kernel with HIP events (ne_profile_enable / ne_profile_read)
     int32_t profile_every;
-    std::vector<hipEvent_t> ev_start, ev_stop;
+    std::vector<hipEvent_t> ev_zero, ev_start, ev_stop;   // zero -> start brackets nothing: the events' own cost
     size_t ev_used;
 };
 
@@ -66,6 +66,22 @@ struct ne_alias {
     int64_t n;
     int32_t base;
 };
+
+// Timing of one kernel with HIP events.  profile_begin records two events back to back (the gap
+// between them is what recording costs on this stream) and profile_end a third after the kernel.
+inline bool profile_begin(ne_tables* t, hipStream_t st)
+{
+    const bool timed = t->profile_every > 0 && t->batches_done % static_cast<uint64_t>(t->profile_every) == 0 &&
+                       t->ev_used < t->ev_start.size();
+    if (!timed) return false;
+    if (hipEventRecord(t->ev_zero[t->ev_used], st) != hipSuccess) return false;
+    return hipEventRecord(t->ev_start[t->ev_used], st) == hipSuccess;
+}
+
+inline void profile_end(ne_tables* t, hipStream_t st)
+{
+    if (hipEventRecord(t->ev_stop[t->ev_used], st) == hipSuccess) t->ev_used += 1;
+}
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 

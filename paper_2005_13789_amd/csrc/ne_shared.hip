@@ -521,20 +521,11 @@ hipError_t run_shared(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(scores_kernel<D>), hipFuncAttributeMaxDynamicSharedMemorySize,
                             static_cast<int>(lds_bytes));
     if (e != hipSuccess) return e;
-    const bool timed = t->profile_every > 0 && t->batches_done % static_cast<uint64_t>(t->profile_every) == 0 &&
-                       t->ev_used < t->ev_start.size();
-    if (timed) {
-        e = hipEventRecord(t->ev_start[t->ev_used], st);
-        if (e != hipSuccess) return e;
-    }
+    const bool timed = profile_begin(t, st);
     hipLaunchKernelGGL(scores_kernel<D>, dim3(static_cast<unsigned>(w.Bp / kRowTile), neg_split), dim3(kScoreThreads), lds_bytes, st, ca);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (timed) {
-        e = hipEventRecord(t->ev_stop[t->ev_used], st);
-        if (e != hipSuccess) return e;
-        t->ev_used += 1;
-    }
+    if (timed) profile_end(t, st);
     t->batches_done += 1;
 
     DctxArgs da{};
