@@ -178,6 +178,18 @@ ne_status ne_eval_loss(const ne_tables* tables, const ne_alias* alias, const int
                        int32_t* neg_out_dev, void* hip_stream);
 
 /*
+ * Sub-part training (Sec. III-B: a GPU's vertex embeddings are split into k sub-parts; one is trained
+ * while the others travel between host and device through ping-pong buffers).  Tells the handle that
+ * vertex rows [first_row, first_row + num_rows) now live at vertex_window_dev (fp32 [num_rows][dim],
+ * device, 16-byte aligned, caller-owned); every later call on the handle must only name source ids
+ * inside that window (ids outside it are undefined behaviour, as out-of-range ids are).  The context
+ * table is unaffected.  Host-side only: nothing is enqueued, so the caller orders the switch against
+ * its own copies with streams and events.  Errors: NE_ERR_ARG.
+ */
+ne_status ne_set_vertex_window(ne_tables* tables, float* vertex_window_dev, int64_t first_row,
+                               int64_t num_rows);
+
+/*
  * Debug helper for the sample format of Table I: counts ids in pairs_dev int32[B][2] that fall
  * outside [0, num_nodes) and adds the count to *bad_count_dev (device uint64, caller-zeroed).
  */

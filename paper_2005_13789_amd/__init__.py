@@ -26,7 +26,7 @@ NE_MAX_BATCH = 1 << 22
 
 EXPORTS = (
     "ne_create_tables", "ne_build_neg_alias", "ne_workspace_bytes", "ne_train_batch", "ne_train_block",
-    "ne_shared_workspace_bytes", "ne_train_batch_shared", "ne_train_batch_async", "ne_eval_loss",
+    "ne_shared_workspace_bytes", "ne_train_batch_shared", "ne_train_batch_async", "ne_set_vertex_window", "ne_eval_loss",
     "ne_validate_pairs", "ne_profile_enable", "ne_profile_read", "ne_destroy_tables", "ne_destroy_alias", "ne_last_error",
 )
 
@@ -68,6 +68,8 @@ def lib() -> ctypes.CDLL:
     L.ne_train_batch_shared.restype = c.c_int
     L.ne_train_batch_async.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_float, c.c_uint64, vp, vp]
     L.ne_train_batch_async.restype = c.c_int
+    L.ne_set_vertex_window.argtypes = [vp, vp, c.c_int64, c.c_int64]
+    L.ne_set_vertex_window.restype = c.c_int
     L.ne_eval_loss.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_uint64, vp, vp, vp]
     L.ne_eval_loss.restype = c.c_int
     L.ne_validate_pairs.argtypes = [vp, vp, c.c_int64, vp, vp]
@@ -216,6 +218,15 @@ def ne_train_batch_async(tables: Tables, alias: Alias | None, pairs: torch.Tenso
         raise TypeError("neg_out needs B*K int32 elements")
     _check(lib().ne_train_batch_async(tables.handle, alias.handle if alias else None, pp, B, K, lr, sample_base,
                                       np_, _stream_ptr(stream)))
+
+
+def ne_set_vertex_window(tables: Tables, window: torch.Tensor, first_row: int) -> None:
+    """Vertex rows [first_row, first_row + len(window)) now live in `window` (CUDA fp32 [rows][dim])."""
+    wp = _dev_ptr(window, torch.float32, "window")
+    if window.dim() != 2 or window.shape[1] != tables.dim:
+        raise TypeError("window must be [rows][dim]")
+    _check(lib().ne_set_vertex_window(tables.handle, wp, first_row, int(window.shape[0])))
+    tables.vertex_window = window      # keep it alive while the handle points at it
 
 
 def ne_shared_workspace_bytes(dim: int, B: int, N: int) -> int:

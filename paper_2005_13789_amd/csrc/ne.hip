@@ -1047,6 +1047,17 @@ ne_status ne_eval_loss(const ne_tables* t, const ne_alias* al, const int32_t* pa
     return NE_OK;
 }
 
+ne_status ne_set_vertex_window(ne_tables* t, float* vertex_window_dev, int64_t first_row, int64_t num_rows)
+{
+    if (!t) return fail(NE_ERR_ARG, "tables handle is NULL");
+    if (!vertex_window_dev || !aligned(vertex_window_dev, 16)) return fail(NE_ERR_ARG, "vertex_window_dev is NULL or not 16-byte aligned");
+    if (first_row < 0 || num_rows <= 0 || first_row + num_rows > t->num_nodes)
+        return fail(NE_ERR_ARG, "window [first_row, first_row + num_rows) is not inside [0, num_nodes)");
+    // the kernels index vertex rows by absolute id: point them at where row 0 would be
+    t->vertex = vertex_window_dev - first_row * static_cast<int64_t>(t->dim);
+    return NE_OK;
+}
+
 ne_status ne_validate_pairs(const ne_tables* t, const int32_t* pairs_dev, int64_t B,
                             unsigned long long* bad_count_dev, void* hip_stream)
 {
