@@ -103,7 +103,7 @@ struct PrepArgs {
 // runs kPrepUnroll references at once: a block covers 256 * kPrepUnroll consecutive references.
 constexpr int kPrepUnroll = 4;
 
-__device__ __forceinline__ void claim_refs(const PrepArgs& a, unsigned block)
+__device__ __forceinline__ void claim_refs(const PrepArgs& a, unsigned block, unsigned tid)
 {
     const uint32_t R = static_cast<uint32_t>(a.K + 2);
     uint32_t t[kPrepUnroll], b[kPrepUnroll];
@@ -114,7 +114,7 @@ __device__ __forceinline__ void claim_refs(const PrepArgs& a, unsigned block)
     uint64_t draw_slot[kPrepUnroll];
 #pragma unroll
     for (int u = 0; u < kPrepUnroll; ++u) {
-        t[u] = (block * kPrepUnroll + u) * 256u + threadIdx.x;
+        t[u] = (block * kPrepUnroll + u) * 256u + tid;
         b[u] = t[u] / R;
         j[u] = static_cast<int>(t[u] - b[u] * R);
         id[u] = 0;
@@ -198,7 +198,7 @@ __device__ __forceinline__ bool fused_block(unsigned extra, unsigned period, uns
     return false;
 }
 
-__global__ __launch_bounds__(256) void claim_kernel(PrepArgs a) { claim_refs(a, blockIdx.x); }
+__global__ __launch_bounds__(256) void claim_kernel(PrepArgs a) { claim_refs(a, blockIdx.x, threadIdx.x); }
 __global__ __launch_bounds__(256) void resolve_kernel(PrepArgs a) { resolve_refs(a, blockIdx.x); }
 
 // ---------------------------------------------------------------------------------------------
@@ -231,15 +231,20 @@ __device__ __forceinline__ void to_consecutive(const float4 (&v)[NCH], float (&o
     __builtin_amdgcn_wave_barrier();
 }
 
+#ifndef NE_TRAIN_THREADS
+#define NE_TRAIN_THREADS 256
+#endif
+constexpr int kTrainThreads = NE_TRAIN_THREADS;   // threads per block of the train kernel (a claim block's 256-thread share is looped)
+
 template <int G, int NCH, int JB>
-__global__ __launch_bounds__(256) void train_kernel(TrainArgs a, PrepArgs next, unsigned claim_blocks, unsigned period)
+__global__ __launch_bounds__(kTrainThreads) void train_kernel(TrainArgs a, PrepArgs next, unsigned claim_blocks, unsigned period)
 {
-    constexpr int GROUPS = 256 / G;
+    constexpr int GROUPS = kTrainThreads / G;
     __shared__ float lds[GROUPS][4 * G * NCH];
     // some blocks do the id-only claim phase of the next batch
     unsigned block;
     if (fused_block(claim_blocks, period, &block)) {
-        claim_refs(next, block);
+        for (unsigned tid = threadIdx.x; tid < 256u; tid += kTrainThreads) claim_refs(next, block, tid);
         return;
     }
     const int lg = threadIdx.x & (G - 1);
@@ -634,13 +639,13 @@ bool pick_shape(int32_t d4, int32_t K, Shape* out)
 
 hipError_t launch_train(const Shape& s, const TrainArgs& a, const PrepArgs& next, hipStream_t st)
 {
-    const int groups = 256 / s.G;
+    const int groups = kTrainThreads / s.G;
     const unsigned claim_blocks = prep_blocks(next.refs);
     const unsigned grid = claim_blocks + static_cast<unsigned>((a.B + groups - 1) / groups);
     const unsigned period = claim_blocks ? grid / claim_blocks : 1u;
 #define NE_CASE(G_, N_)                                                                          \
     if (s.G == G_ && s.NCH == N_) {                                                              \
-        hipLaunchKernelGGL((train_kernel<G_, N_, 6>), dim3(grid), dim3(256), 0, st, a, next, claim_blocks, period); \
+        hipLaunchKernelGGL((train_kernel<G_, N_, 6>), dim3(grid), dim3(kTrainThreads), 0, st, a, next, claim_blocks, period); \
         return hipGetLastError();                                                                \
     }
     NE_FOR_EACH_SHAPE(NE_CASE)
