@@ -13,11 +13,14 @@
 // Four kernels per batch:
 //   stage   gathers and rounds the rows, draws the N negatives, does the positive pairs in fp32 and
 //           stages their deltas; the tables are only read.
-//   scores  one workgroup per 64 pairs and share of the negatives: S tile by tile on MFMA, sigmoid in registers, G to LDS (and
-//           transposed to memory for the dC product), dX accumulated on MFMA over all N negatives.
+//   scores  one workgroup per 128 pairs and share of the negatives: S tile by tile on MFMA, sigmoid
+//           in registers, G to LDS (and transposed to memory for the dC product), dX accumulated on
+//           MFMA over the share.
 //   dctx    dC = G^T . Xq on MFMA, split over the batch dimension into partial sums.
-//   update  adds every staged delta to the tables with fp32 atomics (consecutive dwords per lane
-//           group).  Nothing reads the tables any more at that point, so duplicates simply add up.
+//   update  adds every staged delta to the tables.  Nothing reads the tables any more at that point,
+//           so duplicates simply add up: rows named once in the batch (found with the plain-store
+//           claim of the stage kernel and the resolve pass that rides in the scores kernel) are
+//           rewritten with plain stores, the others take fp32 atomics.
 #include <hip/hip_bf16.h>
 
 #include "ne_internal.h"
@@ -58,9 +61,18 @@ struct SharedWs {
     float* dXn;      // [kNegSplit][Bp][d]   partial sums of G . Cq
     float* dCp;      // [kSplit][N][d] partial sums of G^T . Xq
     int32_t* negids; // [N]
+    unsigned long long* slots;   // [hash_mask + 1]  (key << 32 | reference) of the reference that claimed a position last
+    uint8_t* multi;              // [hash_mask + 1]  1 = the row that owns this position is named more than once
+    uint32_t hash_mask;
     int64_t Bp;
     size_t total;
 };
+
+// References of a batch: 2b the source row of pair b, 2b + 1 its context row, 2B + j negative j.
+// key = row | (context table ? 1 << 31 : 0).
+__device__ __forceinline__ uint32_t ref_hash(uint32_t key, uint32_t mask) { return ((key * 0x9E3779B1u) >> 9) & mask; }
+__device__ __forceinline__ unsigned long long ref_entry(uint32_t key, uint32_t ref) { return (static_cast<unsigned long long>(key) << 32) | ref; }
+constexpr uint32_t kContextKey = 0x80000000u;
 
 bool shared_layout(int32_t dim, int64_t B, int32_t N, char* base, SharedWs* w)
 {
@@ -82,6 +94,11 @@ bool shared_layout(int32_t dim, int64_t B, int32_t N, char* base, SharedWs* w)
     w->dXn = reinterpret_cast<float*>(take(static_cast<size_t>(kNegSplit) * Bp * d * 4));
     w->dCp = reinterpret_cast<float*>(take(static_cast<size_t>(kSplit) * n * d * 4));
     w->negids = reinterpret_cast<int32_t*>(take(n * 4));
+    size_t cap = 4096;
+    while (cap < 4 * (2 * Bp + n)) cap <<= 1;
+    w->hash_mask = static_cast<uint32_t>(cap - 1);
+    w->slots = reinterpret_cast<unsigned long long*>(take(cap * 8));
+    w->multi = reinterpret_cast<uint8_t*>(take(cap));
     w->total = off;
     return true;
 }
@@ -116,11 +133,22 @@ __global__ __launch_bounds__(256) void stage_kernel(StageArgs a)
     const int lg = threadIdx.x & (G - 1);
     const int64_t gidx = static_cast<int64_t>(blockIdx.x) * GROUPS + threadIdx.x / G;
     float loss_term = 0.0f;
+    // the "named more than once" flags start from zero in every batch (16 per thread; the grid has
+    // more than (2 Bp + N) * 8 threads and the flag array 4..8 times (2 Bp + N) bytes)
+    {
+        const size_t i = (static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x) * 16;
+        if (i <= a.w.hash_mask) *reinterpret_cast<uint4*>(a.w.multi + i) = make_uint4(0u, 0u, 0u, 0u);
+    }
     if (gidx < a.Bp) {
         const int64_t b = gidx;
         uint2* xq = reinterpret_cast<uint2*>(a.w.Xq + b * D);
         if (b < a.B) {
             const int2 pr = a.pairs[b];
+            // claim: whichever reference stores last owns the position of its row's key
+            if (lg < 2) {
+                const uint32_t key = lg == 0 ? static_cast<uint32_t>(pr.x) : (static_cast<uint32_t>(pr.y) | kContextKey);
+                a.w.slots[ref_hash(key, a.w.hash_mask)] = ref_entry(key, static_cast<uint32_t>(2 * b + lg));
+            }
             const float4* xrow = a.X + static_cast<int64_t>(pr.x) * D4;
             const float4* crow = a.C + static_cast<int64_t>(pr.y) * D4;
             float4 x[2], c[2];
@@ -151,6 +179,8 @@ __global__ __launch_bounds__(256) void stage_kernel(StageArgs a)
         if (lg == 0) {
             a.w.negids[j] = id;
             if (a.neg_out) a.neg_out[j] = id;
+            const uint32_t key = static_cast<uint32_t>(id) | kContextKey;
+            a.w.slots[ref_hash(key, a.w.hash_mask)] = ref_entry(key, static_cast<uint32_t>(2 * a.B + j));
         }
         const float4* crow = a.C + static_cast<int64_t>(id) * D4;
         uint2* cq = reinterpret_cast<uint2*>(a.w.Cq + static_cast<int64_t>(j) * D);
@@ -192,6 +222,7 @@ struct ScoresArgs {
     int32_t N;
     float neg_scale;
     double* loss;
+    const int2* pairs;
 };
 
 template <int D>
@@ -210,6 +241,25 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(ScoresArgs a)
     const int rh = w & 3, ch = w >> 2;   // 32-pair quarter, half of the chunk / of the columns
     const int64_t b0 = static_cast<int64_t>(blockIdx.x) * kRowTile;
     const int64_t Bp = a.w.Bp;
+
+    // resolve (ids only, a by-product of this launch): a reference that finds its row's key at the
+    // key's position under another reference's name flags the row as named more than once
+    {
+        const int64_t refs = 2 * a.B + a.N;
+        const int64_t stride = static_cast<int64_t>(gridDim.x) * gridDim.y * kScoreThreads;
+        for (int64_t r = (static_cast<int64_t>(blockIdx.y) * gridDim.x + blockIdx.x) * kScoreThreads + tid; r < refs; r += stride) {
+            uint32_t key;
+            if (r < 2 * a.B) {
+                const int2 pr = a.pairs[r >> 1];
+                key = (r & 1) ? (static_cast<uint32_t>(pr.y) | kContextKey) : static_cast<uint32_t>(pr.x);
+            } else {
+                key = static_cast<uint32_t>(a.w.negids[r - 2 * a.B]) | kContextKey;
+            }
+            const uint32_t pos = ref_hash(key, a.w.hash_mask);
+            const unsigned long long owner = a.w.slots[pos];
+            if (static_cast<uint32_t>(owner >> 32) == key && static_cast<uint32_t>(owner) != static_cast<uint32_t>(r)) a.w.multi[pos] = 1;
+        }
+    }
 
     // the source rows of this workgroup
     for (int c = tid; c < kRowTile * (D / 8); c += kScoreThreads) {
@@ -442,8 +492,12 @@ __global__ __launch_bounds__(256) void dctx_kernel(DctxArgs a)
 }
 
 // ---------------------------------------------------------------------------------------------
-// update kernel: one lane group of G = D/8 lanes per pair / per negative; lane lg owns elements
-// lg + m*G, so every atomic instruction of a group covers consecutive dwords.
+// update kernel: one lane group of G = D/8 lanes per pair / per negative.  Nothing reads the tables
+// any more, so every staged delta is simply added to its row.  fp32 atomics retire far more slowly
+// than plain stores on this chip, so a row that a single reference of the batch names (it owns its
+// key's position and nobody flagged it) is read, added to and stored back in float4 pieces; only
+// rows named more than once, and the few whose key lost its position to another row, take atomics
+// (lane lg then owns elements lg + m*G, so each atomic instruction covers consecutive dwords).
 // ---------------------------------------------------------------------------------------------
 struct UpdateArgs {
     float* X;
@@ -456,6 +510,14 @@ struct UpdateArgs {
     SharedWs w;
 };
 
+__device__ __forceinline__ bool sole_reference(const SharedWs& w, uint32_t key, uint32_t ref)
+{
+    const uint32_t pos = ref_hash(key, w.hash_mask);
+    return w.slots[pos] == ref_entry(key, ref) && w.multi[pos] == 0;
+}
+
+__device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
+
 template <int D>
 __global__ __launch_bounds__(256) void update_shared_kernel(UpdateArgs a)
 {
@@ -465,32 +527,96 @@ __global__ __launch_bounds__(256) void update_shared_kernel(UpdateArgs a)
     const int64_t gidx = static_cast<int64_t>(blockIdx.x) * GROUPS + threadIdx.x / G;
     if (gidx < a.B) {
         const int2 pr = a.pairs[gidx];
+        const bool x_sole = sole_reference(a.w, static_cast<uint32_t>(pr.x), static_cast<uint32_t>(2 * gidx));
+        const bool c_sole = sole_reference(a.w, static_cast<uint32_t>(pr.y) | kContextKey, static_cast<uint32_t>(2 * gidx + 1));
         float* xrow = a.X + static_cast<int64_t>(pr.x) * D;
         float* crow = a.C + static_cast<int64_t>(pr.y) * D;
         const float* dxp = a.w.dxp + gidx * D;
         const float* dxn = a.w.dXn + gidx * D;
         const int64_t part = a.w.Bp * D;
         const float* uctx = a.w.uctx + gidx * D;
+        // all loads of a group are issued before its first store or atomic
+        float4 x4[2], c4[2];
+        float x1[8], c1[8];
+        if (x_sole) {
 #pragma unroll
-        for (int m = 0; m < 8; ++m) {
-            const int e = lg + m * G;
-            float neg_part = 0.0f;
+            for (int i = 0; i < 2; ++i) {
+                const int ci = lg + i * G;
+                float4 n = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-            for (int s = 0; s < kNegSplit; ++s)
-                if (s < a.neg_split) neg_part += dxn[s * part + e];
-            unsafeAtomicAdd(xrow + e, fmaf(a.lr, neg_part, dxp[e]));
-            unsafeAtomicAdd(crow + e, uctx[e]);
+                for (int s = 0; s < kNegSplit; ++s)
+                    if (s < a.neg_split) n = add4(n, reinterpret_cast<const float4*>(dxn + s * part)[ci]);
+                const float4 p = reinterpret_cast<const float4*>(dxp)[ci];
+                const float4 r = reinterpret_cast<const float4*>(xrow)[ci];
+                x4[i] = make_float4(r.x + fmaf(a.lr, n.x, p.x), r.y + fmaf(a.lr, n.y, p.y), r.z + fmaf(a.lr, n.z, p.z),
+                                    r.w + fmaf(a.lr, n.w, p.w));
+            }
+        } else {
+#pragma unroll
+            for (int m = 0; m < 8; ++m) {
+                const int e = lg + m * G;
+                float n = 0.0f;
+#pragma unroll
+                for (int s = 0; s < kNegSplit; ++s)
+                    if (s < a.neg_split) n += dxn[s * part + e];
+                x1[m] = fmaf(a.lr, n, dxp[e]);
+            }
+        }
+        if (c_sole) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int ci = lg + i * G;
+                c4[i] = add4(reinterpret_cast<const float4*>(crow)[ci], reinterpret_cast<const float4*>(uctx)[ci]);
+            }
+        } else {
+#pragma unroll
+            for (int m = 0; m < 8; ++m) c1[m] = uctx[lg + m * G];
+        }
+        if (x_sole) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) reinterpret_cast<float4*>(xrow)[lg + i * G] = x4[i];
+        } else {
+#pragma unroll
+            for (int m = 0; m < 8; ++m) unsafeAtomicAdd(xrow + lg + m * G, x1[m]);
+        }
+        if (c_sole) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) reinterpret_cast<float4*>(crow)[lg + i * G] = c4[i];
+        } else {
+#pragma unroll
+            for (int m = 0; m < 8; ++m) unsafeAtomicAdd(crow + lg + m * G, c1[m]);
         }
     } else if (gidx < a.B + a.N) {
         const int64_t j = gidx - a.B;
-        float* crow = a.C + static_cast<int64_t>(a.w.negids[j]) * D;
+        const int32_t id = a.w.negids[j];
+        const bool sole = sole_reference(a.w, static_cast<uint32_t>(id) | kContextKey, static_cast<uint32_t>(2 * a.B + j));
+        float* crow = a.C + static_cast<int64_t>(id) * D;
+        if (sole) {
+            float4 c4[2];
 #pragma unroll
-        for (int m = 0; m < 8; ++m) {
-            const int e = lg + m * G;
-            float sum = 0.0f;
+            for (int i = 0; i < 2; ++i) {
+                const int ci = lg + i * G;
+                float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-            for (int s = 0; s < kSplit; ++s) sum += a.w.dCp[(static_cast<int64_t>(s) * a.N + j) * D + e];
-            unsafeAtomicAdd(crow + e, a.lr * sum);
+                for (int s = 0; s < kSplit; ++s)
+                    sum = add4(sum, reinterpret_cast<const float4*>(a.w.dCp + (static_cast<int64_t>(s) * a.N + j) * D)[ci]);
+                const float4 r = reinterpret_cast<const float4*>(crow)[ci];
+                c4[i] = make_float4(fmaf(a.lr, sum.x, r.x), fmaf(a.lr, sum.y, r.y), fmaf(a.lr, sum.z, r.z), fmaf(a.lr, sum.w, r.w));
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i) reinterpret_cast<float4*>(crow)[lg + i * G] = c4[i];
+        } else {
+            float c1[8];
+#pragma unroll
+            for (int m = 0; m < 8; ++m) {
+                const int e = lg + m * G;
+                float sum = 0.0f;
+#pragma unroll
+                for (int s = 0; s < kSplit; ++s) sum += a.w.dCp[(static_cast<int64_t>(s) * a.N + j) * D + e];
+                c1[m] = a.lr * sum;
+            }
+#pragma unroll
+            for (int m = 0; m < 8; ++m) unsafeAtomicAdd(crow + lg + m * G, c1[m]);
         }
     }
 }
@@ -515,7 +641,7 @@ hipError_t run_shared(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev
     // shares of the negatives must be whole 64-negative chunks
     const unsigned neg_split = (N % (kNegSplit * kNegChunk) == 0) ? kNegSplit : 2;
     ScoresArgs ca{};
-    ca.w = w; ca.B = B; ca.N = N; ca.neg_scale = neg_scale; ca.loss = loss;
+    ca.w = w; ca.B = B; ca.N = N; ca.neg_scale = neg_scale; ca.loss = loss; ca.pairs = sa.pairs;
     const size_t lds_bytes = (static_cast<size_t>(kRowTile + kNegChunk) * (D + 8) + static_cast<size_t>(D + kRowTile) * (kNegChunk + 8)) * 2;
     // more than the default 64 KB of dynamic LDS (gfx950 has 160 KB per CU)
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(scores_kernel<D>), hipFuncAttributeMaxDynamicSharedMemorySize,

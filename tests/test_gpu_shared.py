@@ -73,6 +73,59 @@ def test_shared_negative_step(V, d, B, N, batches):
         vertex.copy_(torch.from_numpy(Xo)); context.copy_(torch.from_numpy(Co))
 
 
+@pytest.mark.parametrize("case", ["all_unique", "one_negative_row", "all_pairs_equal"])
+def test_shared_row_sharing_classes(case):
+    """Rows named once are rewritten with plain stores, rows named more than once take atomics: the three
+    extremes, each from a workspace full of garbage (it needs no initialisation)."""
+    say(f"shared-negative row sharing: {case}")
+    V, d, B, N = 60000, 128, 2000, 128
+    rng = np.random.default_rng(5)
+    seed = 3
+    if case == "one_negative_row":
+        deg = np.zeros(V, np.uint32); deg[77] = 9            # every negative is row 77
+    else:
+        deg = np.ones(V, np.uint32)
+    if case == "all_unique":
+        perm = rng.permutation(V).astype(np.int32)
+        pairs = np.stack([perm[:B], perm[B:2 * B]], axis=1)  # no row twice among the pairs
+    elif case == "one_negative_row":
+        pairs = rng.integers(0, V, (B, 2)).astype(np.int32)
+        pairs[::7, 1] = 77                                   # the negatives' row is also a positive context
+        pairs[::5, 0] = pairs[0, 0]                          # and one source row is named 400 times
+    else:
+        pairs = np.tile(np.array([[123, 456]], np.int32), (B, 1))
+    pairs = np.ascontiguousarray(pairs)
+    X = rng.normal(0, 1.5 / np.sqrt(d), (V, d)).astype(np.float32)
+    C = rng.normal(0, 1.5 / np.sqrt(d), (V, d)).astype(np.float32)
+    vertex, context = torch.from_numpy(X).to(DEV), torch.from_numpy(C).to(DEV)
+    t = ne.ne_create_tables(vertex, context, seed, init=False)
+    at = torch.empty((V, 2), dtype=torch.int32, device=DEV)
+    alias = ne.ne_build_neg_alias(deg, 0, at)
+    ws = torch.full((ne.ne_shared_workspace_bytes(d, B, N),), 0xFF, dtype=torch.uint8, device=DEV)
+    neg_dev = torch.empty(N, dtype=torch.int32, device=DEV)
+    thr, al, _ = oracle.build_alias(deg)
+    lr, scale = 0.02, 5.0 / N
+    Xo, Co = X.copy(), C.copy()
+    for it in range(2):                                      # second call: the workspace holds the first call's state
+        Xb, Cb = Xo.copy(), Co.copy()
+        ne.ne_train_batch_shared(t, alias, torch.from_numpy(pairs).to(DEV), N, lr, scale, it, ws, neg_dev)
+        torch.cuda.synchronize()
+        negs = oracle.sample_shared_negatives(seed, it, N, thr, al)
+        assert np.array_equal(neg_dev.cpu().numpy(), negs)
+        if case == "one_negative_row":
+            assert (negs == 77).all()
+        oracle.train_batch_shared(Xo, Co, pairs, negs, lr, scale, bf16_inputs=True)
+        Xg, Cg = vertex.cpu().numpy(), context.cpu().numpy()
+        ex, ec = delta_err(Xb, Xg, Xo), delta_err(Cb, Cg, Co)
+        say(f"  call {it}: delta err X {ex:.2e} C {ec:.2e}")
+        assert ex <= 2e-4 and ec <= 2e-4
+        touched_x = np.zeros(V, bool); touched_x[pairs[:, 0]] = True
+        touched_c = np.zeros(V, bool); touched_c[pairs[:, 1]] = True; touched_c[negs] = True
+        assert np.array_equal(Xg[~touched_x].view(np.uint32), Xb[~touched_x].view(np.uint32))
+        assert np.array_equal(Cg[~touched_c].view(np.uint32), Cb[~touched_c].view(np.uint32))
+        vertex.copy_(torch.from_numpy(Xo)); context.copy_(torch.from_numpy(Co))
+
+
 def test_shared_argument_errors():
     V, d = 500, 128
     vertex = torch.zeros((V, d), dtype=torch.float32, device=DEV)
