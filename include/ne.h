@@ -190,6 +190,16 @@ ne_status ne_set_vertex_window(ne_tables* tables, float* vertex_window_dev, int6
                                int64_t num_rows);
 
 /*
+ * Evaluation helper (link prediction, Sec. V-B): the similarity score of arbitrary node pairs at the
+ * current tables,  scores_dev[i] = vertex[pairs[i][0]] . second[pairs[i][1]]  in fp32, where second is
+ * the context table (second_from_context != 0: the score the training objective uses) or the vertex
+ * table (0).  pairs_dev int32[n][2] and scores_dev float[n] are device buffers of the caller; ids are
+ * not range-checked.  The tables are only read.  n == 0 is a no-op.  Errors: NE_ERR_ARG, NE_ERR_HIP.
+ */
+ne_status ne_score_pairs(const ne_tables* tables, const int32_t* pairs_dev, int64_t n,
+                         int32_t second_from_context, float* scores_dev, void* hip_stream);
+
+/*
  * Debug helper for the sample format of Table I: counts ids in pairs_dev int32[B][2] that fall
  * outside [0, num_nodes) and adds the count to *bad_count_dev (device uint64, caller-zeroed).
  */

@@ -61,6 +61,8 @@ def _bind(lib):
     lib.oracle_train_batch_shared.restype = c.c_int
     lib.oracle_train_sequential.argtypes = [p, p, c.c_int64, c.c_int32, p, c.c_int64, c.c_int32, c.c_float, p]
     lib.oracle_train_sequential.restype = c.c_int
+    lib.oracle_score_pairs.argtypes = [p, p, c.c_int32, p, c.c_int64, c.c_int32, p]
+    lib.oracle_score_pairs.restype = None
     lib.oracle_eval_loss.argtypes = [p, p, c.c_int64, c.c_int32, p, c.c_int64, c.c_int32, p]
     lib.oracle_eval_loss.restype = c.c_double
     return lib
@@ -194,3 +196,14 @@ def train_sequential(X: np.ndarray, C: np.ndarray, pairs: np.ndarray, neg: np.nd
     rc = _load().oracle_train_sequential(_ptr(X), _ptr(C), V, d, _ptr(pairs), B, K, np.float32(lr), _ptr(neg))
     if rc != 0:
         raise ValueError(f"oracle_train_sequential failed ({rc})")
+
+
+def score_pairs(X: np.ndarray, C: np.ndarray, pairs: np.ndarray, second_from_context: bool = True) -> np.ndarray:
+    """float64[n]: X[pairs[i,0]] . (C if second_from_context else X)[pairs[i,1]]."""
+    _chk(X, np.float32, "X")
+    _chk(C, np.float32, "C")
+    _chk(pairs, np.int32, "pairs")
+    out = np.empty(pairs.shape[0], dtype=np.float64)
+    _load().oracle_score_pairs(_ptr(X), _ptr(C), X.shape[1], _ptr(pairs), pairs.shape[0],
+                               1 if second_from_context else 0, _ptr(out))
+    return out

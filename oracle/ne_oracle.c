@@ -28,7 +28,8 @@
  * Pins (tests/, -m "not gpu"): finite differences and torch-CPU autograd for the
  * update, closed forms for the loss and for the first batch from a zero context
  * table, exact integer identity + 10^7-draw frequencies for the alias table,
- * rocRAND's host-callable Philox engine and big-integer arithmetic for Philox.
+ * rocRAND's host-callable Philox engine and big-integer arithmetic for Philox,
+ * hand values and the loss function's positive term for the pair score.
  * Parity unpinned: none of the functions below.
  */
 #include <math.h>
@@ -418,4 +419,20 @@ int oracle_train_sequential(float* X, float* C, int64_t V, int32_t d, const int3
     }
     free(dx); free(g); free(xs);
     return 0;
+}
+
+/* Similarity score of arbitrary node pairs (evaluation for link prediction, Sec. V-B): the dot
+ * product of the first node's vertex row with the second node's context row (second_from_context)
+ * or vertex row, accumulated in fp64 in index order. */
+void oracle_score_pairs(const float* X, const float* C, int32_t d, const int32_t* pairs, int64_t n,
+                        int32_t second_from_context, double* scores_out)
+{
+    const float* S = second_from_context ? C : X;
+    for (int64_t i = 0; i < n; ++i) {
+        const float* a = X + (int64_t)pairs[2 * i] * d;
+        const float* b = S + (int64_t)pairs[2 * i + 1] * d;
+        double acc = 0.0;
+        for (int32_t k = 0; k < d; ++k) acc += (double)a[k] * (double)b[k];
+        scores_out[i] = acc;
+    }
 }

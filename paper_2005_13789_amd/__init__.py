@@ -27,7 +27,7 @@ NE_MAX_BATCH = 1 << 22
 EXPORTS = (
     "ne_create_tables", "ne_build_neg_alias", "ne_workspace_bytes", "ne_train_batch", "ne_train_block",
     "ne_shared_workspace_bytes", "ne_train_batch_shared", "ne_train_batch_async", "ne_set_vertex_window", "ne_eval_loss",
-    "ne_validate_pairs", "ne_profile_enable", "ne_profile_read", "ne_destroy_tables", "ne_destroy_alias", "ne_last_error",
+    "ne_score_pairs", "ne_validate_pairs", "ne_profile_enable", "ne_profile_read", "ne_destroy_tables", "ne_destroy_alias", "ne_last_error",
 )
 
 _lib = None
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
     L.ne_set_vertex_window.restype = c.c_int
     L.ne_eval_loss.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_uint64, vp, vp, vp]
     L.ne_eval_loss.restype = c.c_int
+    L.ne_score_pairs.argtypes = [vp, vp, c.c_int64, c.c_int32, vp, vp]
+    L.ne_score_pairs.restype = c.c_int
     L.ne_validate_pairs.argtypes = [vp, vp, c.c_int64, vp, vp]
     L.ne_validate_pairs.restype = c.c_int
     L.ne_profile_enable.argtypes = [vp, c.c_int32, c.c_int32]
@@ -261,6 +263,17 @@ def ne_eval_loss(tables: Tables, alias: Alias | None, pairs: torch.Tensor, K: in
         raise TypeError("neg_out needs B*K int32 elements")
     _check(lib().ne_eval_loss(tables.handle, alias.handle if alias else None, pp, B, K, sample_base, lp, np_,
                               _stream_ptr(stream)))
+
+
+def ne_score_pairs(tables: Tables, pairs: torch.Tensor, scores: torch.Tensor, second_from_context: bool = True,
+                   stream=None) -> None:
+    """scores[i] = vertex[pairs[i,0]] . (context if second_from_context else vertex)[pairs[i,1]] (CUDA float32[n])."""
+    pp = _dev_ptr(pairs, torch.int32, "pairs")
+    sp = _dev_ptr(scores, torch.float32, "scores")
+    if scores.numel() < pairs.shape[0]:
+        raise ValueError("scores is shorter than pairs")
+    _check(lib().ne_score_pairs(tables.handle, pp, int(pairs.shape[0]), 1 if second_from_context else 0, sp,
+                                _stream_ptr(stream)))
 
 
 def ne_validate_pairs(tables: Tables, pairs: torch.Tensor, bad_count: torch.Tensor, stream=None) -> None:

@@ -621,6 +621,27 @@ __global__ __launch_bounds__(256) void validate_pairs_kernel(const int32_t* __re
 }
 
 // ---------------------------------------------------------------------------------------------
+// score kernel (ne_score_pairs): the model's similarity score of arbitrary node pairs, for
+// evaluation (link prediction, Sec. V-B).  16 lanes per pair, float4 chunks strided over the row.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void score_pairs_kernel(const float4* __restrict__ A, const float4* __restrict__ Bt,
+                                                          const int2* __restrict__ pairs, int64_t n, int32_t d4,
+                                                          float* __restrict__ scores)
+{
+    const int lg = threadIdx.x & 15;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * 16;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * 16 + (threadIdx.x >> 4); i < n; i += stride) {
+        const int2 pr = pairs[i];
+        const float4* a = A + static_cast<int64_t>(pr.x) * d4;
+        const float4* b = Bt + static_cast<int64_t>(pr.y) * d4;
+        float p = 0.0f;
+        for (int c = lg; c < d4; c += 16) p += dot4(a[c], b[c]);
+        p = group_sum<16>(p);
+        if (lg == 0) scores[i] = p;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // launch-shape selection
 // ---------------------------------------------------------------------------------------------
 struct Shape { int G, NCH; };
@@ -1060,6 +1081,25 @@ ne_status ne_set_vertex_window(ne_tables* t, float* vertex_window_dev, int64_t f
         return fail(NE_ERR_ARG, "window [first_row, first_row + num_rows) is not inside [0, num_nodes)");
     // the kernels index vertex rows by absolute id: point them at where row 0 would be
     t->vertex = vertex_window_dev - first_row * static_cast<int64_t>(t->dim);
+    return NE_OK;
+}
+
+ne_status ne_score_pairs(const ne_tables* t, const int32_t* pairs_dev, int64_t n, int32_t second_from_context,
+                         float* scores_dev, void* hip_stream)
+{
+    if (!t) return fail(NE_ERR_ARG, "tables handle is NULL");
+    if (n < 0 || n > (static_cast<int64_t>(1) << 40)) return fail(NE_ERR_ARG, "n out of range");
+    if (n == 0) return NE_OK;
+    if (!pairs_dev || !aligned(pairs_dev, 8)) return fail(NE_ERR_ARG, "pairs_dev is NULL or not 8-byte aligned");
+    if (!scores_dev || !aligned(scores_dev, 4)) return fail(NE_ERR_ARG, "scores_dev is NULL or misaligned");
+    const int64_t want = (n + 15) / 16;
+    const unsigned grid = static_cast<unsigned>(want < 65536 ? want : 65536);
+    hipLaunchKernelGGL(score_pairs_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                       reinterpret_cast<const float4*>(t->vertex),
+                       reinterpret_cast<const float4*>(second_from_context ? t->context : t->vertex),
+                       reinterpret_cast<const int2*>(pairs_dev), n, t->dim / 4, scores_dev);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("score launch: ") + hipGetErrorString(e));
     return NE_OK;
 }
 

@@ -10,6 +10,7 @@ import pytest
 import oracle
 import test_oracle_alias as t_alias
 import test_oracle_philox as t_philox
+import test_oracle_score as t_score
 import test_oracle_sequential as t_seq
 import test_oracle_sgns as t_sgns
 import test_oracle_shared as t_shared
@@ -52,6 +53,10 @@ MUTATIONS = [
      [t_shared.test_shared_with_bf16_rounding_matches_torch_bfloat16]),
     ("sequential mode reuses stale source row", "for (int32_t i = 0; i < d; ++i) x[i] = (float)(xs[i] + dx[i]);",
      "for (int32_t i = 0; i < d; ++i) x[i] = (float)(xs[i] + 0.5 * dx[i]);", [t_seq.test_sequential_equals_batches_of_one]),
+    ("pair score reads the wrong second table", "const float* S = second_from_context ? C : X;",
+     "const float* S = second_from_context ? X : C;", [t_score.test_score_hand_values_and_table_choice]),
+    ("pair score indexes the second node by the first", "const float* b = S + (int64_t)pairs[2 * i + 1] * d;",
+     "const float* b = S + (int64_t)pairs[2 * i] * d;", [t_score.test_score_agrees_with_the_positive_loss_term]),
 ]
 
 
