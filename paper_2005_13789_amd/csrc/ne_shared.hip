@@ -23,6 +23,8 @@
 //           rewritten with plain stores, the others take fp32 atomics.
 #include <hip/hip_bf16.h>
 
+#include <atomic>
+
 #include "ne_internal.h"
 
 namespace {
@@ -643,10 +645,22 @@ hipError_t run_shared(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev
     ScoresArgs ca{};
     ca.w = w; ca.B = B; ca.N = N; ca.neg_scale = neg_scale; ca.loss = loss; ca.pairs = sa.pairs;
     const size_t lds_bytes = (static_cast<size_t>(kRowTile + kNegChunk) * (D + 8) + static_cast<size_t>(D + kRowTile) * (kNegChunk + 8)) * 2;
-    // more than the default 64 KB of dynamic LDS (gfx950 has 160 KB per CU)
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(scores_kernel<D>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            static_cast<int>(lds_bytes));
-    if (e != hipSuccess) return e;
+    // more than the default 64 KB of dynamic LDS (gfx950 has 160 KB per CU): asked for once per device
+    // and kernel, so that later calls are kernel launches only (a caller may be capturing the stream)
+    {
+        static std::atomic<uint64_t> lds_raised{0};
+        int device = 0;
+        e = hipGetDevice(&device);
+        if (e != hipSuccess) return e;
+        const uint64_t bit = 1ull << (device & 63);
+        if (!(lds_raised.load(std::memory_order_acquire) & bit)) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(scores_kernel<D>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    static_cast<int>((static_cast<size_t>(kRowTile + kNegChunk) * (D + 8) +
+                                                      static_cast<size_t>(D + kRowTile) * (kNegChunk + 8)) * 2));
+            if (e != hipSuccess) return e;
+            lds_raised.fetch_or(bit, std::memory_order_release);
+        }
+    }
     const bool timed = profile_begin(t, st);
     hipLaunchKernelGGL(scores_kernel<D>, dim3(static_cast<unsigned>(w.Bp / kRowTile), neg_split), dim3(kScoreThreads), lds_bytes, st, ca);
     e = hipGetLastError();
