@@ -136,7 +136,8 @@ ne_status ne_train_block(ne_tables* tables, const ne_alias* alias, const int32_t
  * Precision: the positive pair is computed in fp32.  For the dense part the gathered rows are rounded
  * to bfloat16 (nearest even), S = Xq . Cq^T accumulates in fp32 on the matrix cores,
  * G = -neg_scale * sigmoid(S) is formed in fp32 and rounded to bfloat16, and G . Cq and G^T . Xq
- * accumulate in fp32; the tables stay fp32 and are updated with fp32 atomic adds.
+ * accumulate in fp32; the tables stay fp32 (rows that one reference of the batch names are rewritten
+ * with plain stores, rows named more than once take fp32 atomic adds, so their sums depend on order).
  *   dim must be 64, 128 or 256; 1 <= B <= 2^20; N a multiple of 128 in [128, 65536].
  *   workspace_dev : device scratch, 256-byte aligned, at least ne_shared_workspace_bytes(dim, B, N)
  *                   bytes, overwritten; needs no initialisation and carries nothing between calls.
