@@ -147,3 +147,46 @@ def test_config3_sampled_rows():
         assert int(neg.min()) >= lo and int(neg.max()) < hi
         want = oracle.sample_negatives(seed, 1000 * k, 2048, K, thr, al, lo)
         assert np.array_equal(neg[:2048].cpu().numpy(), want)
+
+
+def test_maximum_batch_size():
+    """One batch of NE_MAX_BATCH pairs (2^22; 29 M row references, 134 M hash positions) through ne_train_batch
+    and a second one through ne_train_block, every element against the oracle.  A small dimension keeps the
+    per-position delta slots (capacity x dim x 4 bytes) and the oracle's time small.  The heavy tail of the
+    pairs' id distribution wraps around instead of piling up on one id: with 3.5 % of the pairs sharing one source
+    row, the hottest negative row (named 4e5 times in the batch) receives 1.5e4 identical contributions and its
+    running fp32 sum drifts by 1.6e-4 of the row (measured) - a statement about fp32 accumulation of
+    same-sign terms, not about the batch size.  The hottest row is still named 4e5 times here."""
+    V, d, K, B, seed = 3_000_000, 8, 5, ne.NE_MAX_BATCH, 9
+    say(f"maximum batch: B={B} V={V} d={d} K={K}; workspace {ne.ne_workspace_bytes(d, B, K) / 2**30:.1f} GiB")
+    rng = np.random.default_rng(0)
+    deg = (rng.pareto(1.0, V) * 3).astype(np.uint32) + 1
+    pairs = ((rng.pareto(0.9, (2 * B, 2)) * V / 40).astype(np.int64) % V).astype(np.int32)
+    t = make_tables(V, d, K, B, seed)
+    t.context.copy_(torch.randn((V, d), generator=torch.Generator().manual_seed(1)).to(DEV) * 0.1)
+    at = torch.empty((V, 2), dtype=torch.int32, device=DEV)
+    alias = ne.ne_build_neg_alias(deg, 0, at)
+    thr, al, _ = oracle.build_alias(deg)
+    Xo, Co = t.vertex.cpu().numpy(), t.context.cpu().numpy()
+    pd = torch.from_numpy(pairs).to(DEV)
+    neg = torch.empty((B, K), dtype=torch.int32, device=DEV)
+    for it, call in enumerate(("ne_train_batch", "ne_train_block")):
+        p = pd[it * B:(it + 1) * B]
+        if it == 0:
+            ne.ne_train_batch(t, alias, p, K, 0.01, it * B, neg)
+        else:
+            ne.ne_train_block(t, alias, p, B, K, [0.01], it * B, neg)
+        torch.cuda.synchronize()
+        negs = oracle.sample_negatives(seed, it * B, B, K, thr, al)
+        assert np.array_equal(neg.cpu().numpy(), negs)
+        oracle.train_batch(Xo, Co, pairs[it * B:(it + 1) * B], negs, 0.01)
+        ex = rowwise_rel_err(t.vertex.cpu().numpy(), Xo, floor_frac=1e-3)
+        ec = rowwise_rel_err(t.context.cpu().numpy(), Co, floor_frac=1e-3)
+        say(f"  {call}: row error X {ex:.2e} C {ec:.2e}")
+        Cg = t.context.cpu().numpy()
+        err = np.abs(Cg.astype(np.float64) - Co).max(axis=1); den = np.abs(Co).max(axis=1)
+        worst = int(np.argmax(err / np.maximum(den, 1e-3 * den.max())))
+        cnt = int((pairs[it * B:(it + 1) * B, 1] == worst).sum() + (negs == worst).sum())
+        say(f"  worst C row {worst}: named {cnt} times, |row| {den[worst]:.3e}, abs err {err[worst]:.3e}, table max {den.max():.3e}")
+        assert ex <= 1e-4 and ec <= 1e-4
+        t.vertex.copy_(torch.from_numpy(Xo)); t.context.copy_(torch.from_numpy(Co))
