@@ -190,3 +190,75 @@ def test_maximum_batch_size():
         say(f"  worst C row {worst}: named {cnt} times, |row| {den[worst]:.3e}, abs err {err[worst]:.3e}, table max {den.max():.3e}")
         assert ex <= 1e-4 and ec <= 1e-4
         t.vertex.copy_(torch.from_numpy(Xo)); t.context.copy_(torch.from_numpy(Co))
+
+
+def test_config4_sampled_rows():
+    say("config 4: 20M nodes, d=512, K=10, B=32768")
+    V, d, K, B, seed = 20_000_000, 512, 10, 32768, 3
+    rng = np.random.default_rng(1)
+    degree = wl.rmat_degrees(V, 80_000_000, seed, device=DEV)           # a fifth of the edges: same shape, less set-up
+    pairs = wl.rmat_pairs(V, 3 * B, seed, device=DEV)
+    t = make_tables(V, d, K, B, seed)
+    deg = degree.clamp(max=2**32 - 1).cpu().numpy().astype(np.uint32)
+    at = torch.empty((V, 2), dtype=torch.int32, device=DEV)
+    alias = ne.ne_build_neg_alias(deg, 0, at)
+    thr, al, _ = oracle.build_alias(deg)
+    for k in range(3):                                                  # from the initial tables, then from trained ones
+        neg = sampled_row_check(t, alias, pairs[k * B:(k + 1) * B], K, 0.025, k * B, 192, rng)
+        want = oracle.sample_negatives(seed, k * B, 2048, K, thr, al)
+        assert np.array_equal(neg[:2048].cpu().numpy(), want)
+
+
+def test_config5_whole_batch_on_compacted_rows():
+    """Config 5 at full size (50 M nodes, 102 GB of tables).  A batch touches at most 2 B + N rows, so the
+    oracle runs the whole batch on a compact copy of exactly those rows (ids renumbered) and every touched row
+    is compared; a sample of untouched rows must stay bit-identical."""
+    say("config 5: 50M nodes, d=256, B=8192, N=1024 shared negatives")
+    V, d, B, N, seed = 50_000_000, 256, 8192, 1024, 4
+    abc = (0.65, 0.15, 0.15)
+    rng = np.random.default_rng(2)
+    degree = wl.rmat_degrees(V, 200_000_000, seed, abc, device=DEV)     # a fifth of the edges
+    pairs = wl.rmat_pairs(V, 2 * B, seed, abc, device=DEV)
+    vertex = torch.empty((V, d), dtype=torch.float32, device=DEV)
+    context = torch.empty((V, d), dtype=torch.float32, device=DEV)
+    t = ne.ne_create_tables(vertex, context, seed, init=True)
+    context.normal_(0.0, 0.08)                                          # a zero context table would score every pair 0
+    vertex.mul_(30.0)
+    deg = degree.clamp(max=2**32 - 1).cpu().numpy().astype(np.uint32)
+    at = torch.empty((V, 2), dtype=torch.int32, device=DEV)
+    alias = ne.ne_build_neg_alias(deg, 0, at)
+    thr, al, _ = oracle.build_alias(deg)
+    ws = torch.empty(ne.ne_shared_workspace_bytes(d, B, N), dtype=torch.uint8, device=DEV)
+    neg_dev = torch.empty(N, dtype=torch.int32, device=DEV)
+    loss_dev = torch.zeros((), dtype=torch.float64, device=DEV)
+    lr, scale = 0.025, 5.0 / N
+    for it in range(2):
+        p = pairs[it * B:(it + 1) * B]
+        negs = oracle.sample_shared_negatives(seed, it, N, thr, al)
+        negs_t = torch.from_numpy(negs).to(DEV).long()
+        xs, xinv = torch.unique(p[:, 0].long(), return_inverse=True)
+        cs, cinv = torch.unique(torch.cat([p[:, 1].long(), negs_t]), return_inverse=True)
+        n = max(xs.numel(), cs.numel())
+        Xm = np.zeros((n, d), np.float32); Cm = np.zeros((n, d), np.float32)
+        Xm[: xs.numel()] = vertex[xs].cpu().numpy()
+        Cm[: cs.numel()] = context[cs].cpu().numpy()
+        Xb, Cb = Xm.copy(), Cm.copy()
+        mp = np.stack([xinv.cpu().numpy(), cinv[:B].cpu().numpy()], axis=1).astype(np.int32)
+        mn = np.ascontiguousarray(cinv[B:].cpu().numpy().astype(np.int32))
+        probe = torch.from_numpy(rng.integers(0, V, 4096)).to(DEV)
+        probe_c, probe_x = probe[~torch.isin(probe, cs)], probe[~torch.isin(probe, xs)]
+        before_c, before_x = context[probe_c].clone(), vertex[probe_x].clone()
+        loss_dev.zero_()
+        ne.ne_train_batch_shared(t, alias, p, N, lr, scale, it, ws, neg_dev, loss_dev)
+        torch.cuda.synchronize()
+        assert np.array_equal(neg_dev.cpu().numpy(), negs)
+        loss_o = oracle.train_batch_shared(Xm, Cm, mp, mn, lr, scale, bf16_inputs=True)
+        assert abs(loss_dev.item() - loss_o) <= 1e-4 * loss_o
+        gx, gc = vertex[xs].cpu().numpy(), context[cs].cpu().numpy()
+        def derr(before, got, want):
+            dg, do = got.astype(np.float64) - before, want.astype(np.float64) - before
+            return np.abs(dg - do).max() / np.abs(do).max()
+        ex, ec = derr(Xb[: xs.numel()], gx, Xm[: xs.numel()]), derr(Cb[: cs.numel()], gc, Cm[: cs.numel()])
+        say(f"  batch {it}: {xs.numel()} + {cs.numel()} touched rows, delta err X {ex:.2e} C {ec:.2e}, loss/pair {loss_o / B:.4f}")
+        assert ex <= 2e-4 and ec <= 2e-4
+        assert torch.equal(context[probe_c], before_c) and torch.equal(vertex[probe_x], before_x)
