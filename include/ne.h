@@ -126,6 +126,30 @@ ne_status ne_train_block(ne_tables* tables, const ne_alias* alias, const int32_t
                          uint64_t sample_base, int32_t* neg_out_dev, void* hip_stream);
 
 /*
+ * On-device augmentation (Algorithm 1, "network augmentation"; Sec. IV-A variant that merges the
+ * augmentation into a later stage): trains directly on random walks instead of on materialised pairs.
+ * walks_dev is int32 [n_walks][walk_len] (device); entry i of a walk is the source of the samples
+ * (walk[i], walk[i+j]) for 1 <= j <= window with i + j < walk_len, the earlier node being the source; a
+ * sample exists only if both entries are non-negative (pad short walks with -1).  Consecutive groups of
+ * walks_per_batch walks form the batches; each batch is one minibatch-synchronous step over all of its
+ * samples, exactly as ne_train_batch on the same pairs would be, with lr_host[batch].  The negatives of
+ * sample (walk r, entry i, offset j), r counted over the whole call, are drawn for sample index
+ *   sample_base + (r * walk_len + i) * window + (j - 1),
+ * so the result does not depend on how the walks are split into batches beyond the batching itself.
+ * One lane group handles one walk entry: its vertex row is gathered once for its `window` samples and
+ * its delta is written once; walks are 4 bytes per entry where pairs are 8 bytes per sample.
+ *   neg_out_dev : NULL, or device int32 [n_walks][walk_len][window][K]; rows of samples that do not
+ *                 exist are left untouched.
+ * Needs the training workspace of ne_create_tables with
+ *   walks_per_batch * walk_len * (1 + window * (K + 1)) <= max_batch * (max_negatives + 2).
+ * 2 <= walk_len <= 65536, 1 <= window <= 64.  n_walks == 0 is a no-op.
+ * Errors: NE_ERR_ARG, NE_ERR_STATE, NE_ERR_HIP.
+ */
+ne_status ne_train_walks(ne_tables* tables, const ne_alias* alias, const int32_t* walks_dev, int64_t n_walks,
+                         int64_t walks_per_batch, int32_t walk_len, int32_t window, int32_t K,
+                         const float* lr_host, uint64_t sample_base, int32_t* neg_out_dev, void* hip_stream);
+
+/*
  * Shared-negative step: the formulation the paper cites as related work (Sec. VI-B), where all pairs
  * of a mini-batch share one set of negatives so that scoring and both gradient products become dense
  * matrix products.  Every one of the B pairs is scored against the same N negative context rows;

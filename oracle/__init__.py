@@ -63,6 +63,8 @@ def _bind(lib):
     lib.oracle_train_sequential.restype = c.c_int
     lib.oracle_score_pairs.argtypes = [p, p, c.c_int32, p, c.c_int64, c.c_int32, p]
     lib.oracle_score_pairs.restype = None
+    lib.oracle_walk_pairs.argtypes = [p, c.c_int64, c.c_int32, c.c_int32, p, p]
+    lib.oracle_walk_pairs.restype = c.c_int64
     lib.oracle_eval_loss.argtypes = [p, p, c.c_int64, c.c_int32, p, c.c_int64, c.c_int32, p]
     lib.oracle_eval_loss.restype = c.c_double
     return lib
@@ -207,3 +209,13 @@ def score_pairs(X: np.ndarray, C: np.ndarray, pairs: np.ndarray, second_from_con
     _load().oracle_score_pairs(_ptr(X), _ptr(C), X.shape[1], _ptr(pairs), pairs.shape[0],
                                1 if second_from_context else 0, _ptr(out))
     return out
+
+
+def walk_pairs(walks: np.ndarray, window: int):
+    """Samples of walks int32[n][L] (Algorithm 1, augmentation): (pairs int32[m][2], sample index int64[m])."""
+    _chk(walks, np.int32, "walks")
+    n, L = walks.shape
+    pairs = np.empty((n * L * window, 2), dtype=np.int32)
+    sample = np.empty(n * L * window, dtype=np.int64)
+    m = _load().oracle_walk_pairs(_ptr(walks), n, L, window, _ptr(pairs), _ptr(sample))
+    return np.ascontiguousarray(pairs[:m]), np.ascontiguousarray(sample[:m])

@@ -29,7 +29,8 @@
  * update, closed forms for the loss and for the first batch from a zero context
  * table, exact integer identity + 10^7-draw frequencies for the alias table,
  * rocRAND's host-callable Philox engine and big-integer arithmetic for Philox,
- * hand values and the loss function's positive term for the pair score.
+ * hand values and the loss function's positive term for the pair score,
+ * a worked example, the sample count of full walks and a brute-force set for the walk samples.
  * Parity unpinned: none of the functions below.
  */
 #include <math.h>
@@ -435,4 +436,30 @@ void oracle_score_pairs(const float* X, const float* C, int32_t d, const int32_t
         for (int32_t k = 0; k < d; ++k) acc += (double)a[k] * (double)b[k];
         scores_out[i] = acc;
     }
+}
+
+/* Network augmentation (Algorithm 1): the samples of a set of walks.  Entry i of a walk is the source
+ * of the samples (walk[i], walk[i+j]) for 1 <= j <= window with i + j < walk_len; the earlier node
+ * is the source; a sample exists only if both entries are non-negative.  Samples are listed by walk,
+ * then entry, then offset; sample_out receives  (r * walk_len + i) * window + (j - 1)  for each, the
+ * index its negatives are drawn for (relative to the call's first sample index).  pairs_out and
+ * sample_out need room for n_walks * walk_len * window samples.  Returns the number of samples. */
+int64_t oracle_walk_pairs(const int32_t* walks, int64_t n_walks, int32_t walk_len, int32_t window,
+                          int32_t* pairs_out, int64_t* sample_out)
+{
+    int64_t n = 0;
+    for (int64_t r = 0; r < n_walks; ++r) {
+        const int32_t* w = walks + r * (int64_t)walk_len;
+        for (int32_t i = 0; i < walk_len; ++i) {
+            for (int32_t j = 1; j <= window; ++j) {
+                if (i + j >= walk_len) continue;
+                if (w[i] < 0 || w[i + j] < 0) continue;
+                pairs_out[2 * n] = w[i];
+                pairs_out[2 * n + 1] = w[i + j];
+                sample_out[n] = (r * (int64_t)walk_len + i) * (int64_t)window + (j - 1);
+                ++n;
+            }
+        }
+    }
+    return n;
 }

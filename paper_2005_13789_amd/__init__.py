@@ -25,7 +25,7 @@ NE_MAX_NEGATIVES = 62
 NE_MAX_BATCH = 1 << 22
 
 EXPORTS = (
-    "ne_create_tables", "ne_build_neg_alias", "ne_workspace_bytes", "ne_train_batch", "ne_train_block",
+    "ne_create_tables", "ne_build_neg_alias", "ne_workspace_bytes", "ne_train_batch", "ne_train_block", "ne_train_walks",
     "ne_shared_workspace_bytes", "ne_train_batch_shared", "ne_train_batch_async", "ne_set_vertex_window", "ne_eval_loss",
     "ne_score_pairs", "ne_validate_pairs", "ne_profile_enable", "ne_profile_read", "ne_destroy_tables", "ne_destroy_alias", "ne_last_error",
 )
@@ -72,6 +72,9 @@ def lib() -> ctypes.CDLL:
     L.ne_set_vertex_window.restype = c.c_int
     L.ne_eval_loss.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_uint64, vp, vp, vp]
     L.ne_eval_loss.restype = c.c_int
+    L.ne_train_walks.argtypes = [vp, vp, vp, c.c_int64, c.c_int64, c.c_int32, c.c_int32, c.c_int32, c.POINTER(c.c_float),
+                                 c.c_uint64, vp, vp]
+    L.ne_train_walks.restype = c.c_int
     L.ne_score_pairs.argtypes = [vp, vp, c.c_int64, c.c_int32, vp, vp]
     L.ne_score_pairs.restype = c.c_int
     L.ne_validate_pairs.argtypes = [vp, vp, c.c_int64, vp, vp]
@@ -208,6 +211,23 @@ def ne_train_block(tables: Tables, alias: Alias | None, pairs: torch.Tensor, B: 
         raise TypeError("neg_out needs n_pairs*K int32 elements")
     _check(lib().ne_train_block(tables.handle, alias.handle if alias else None, pp, n_pairs, B, K, arr, sample_base,
                                 np_, _stream_ptr(stream)))
+
+
+def ne_train_walks(tables: Tables, alias: Alias | None, walks: torch.Tensor, walks_per_batch: int, window: int, K: int,
+                   lrs, sample_base: int, neg_out: torch.Tensor | None = None, stream=None) -> None:
+    """All of walks int32 [n_walks][walk_len] (CUDA) in consecutive batches of walks_per_batch walks; lrs: one float
+    per batch.  neg_out: int32 [n_walks][walk_len][window][K] or None."""
+    n_walks, walk_len = int(walks.shape[0]), int(walks.shape[1])
+    n_batches = -(-n_walks // walks_per_batch) if walks_per_batch > 0 else 0
+    if len(lrs) < n_batches:
+        raise TypeError("lrs needs one learning rate per batch")
+    arr = (ctypes.c_float * max(n_batches, 1))(*[float(v) for v in lrs[:n_batches]])
+    wp = _dev_ptr(walks, torch.int32, "walks")
+    np_ = _dev_ptr(neg_out, torch.int32, "neg_out")
+    if neg_out is not None and neg_out.numel() < n_walks * walk_len * window * K:
+        raise TypeError("neg_out needs n_walks*walk_len*window*K int32 elements")
+    _check(lib().ne_train_walks(tables.handle, alias.handle if alias else None, wp, n_walks, walks_per_batch, walk_len,
+                                window, K, arr, sample_base, np_, _stream_ptr(stream)))
 
 
 def ne_train_batch_async(tables: Tables, alias: Alias | None, pairs: torch.Tensor, K: int, lr: float,

@@ -83,8 +83,11 @@ constexpr unsigned long long kEmptySlot = ~0ull;
 __device__ __forceinline__ uint32_t hash_key(uint32_t key, uint32_t mask) { return ((key * 0x9E3779B1u) >> 7) & mask; }
 
 struct PrepArgs {
-    const int2* pairs;
-    uint32_t refs;        // B * (K + 2); 0 = nothing to prepare
+    const int2* pairs;    // pair mode: the batch's pairs
+    const int32_t* walks; // walk mode (pairs == nullptr): the batch's walks, int32 [..][walk_len]
+    int32_t walk_len, window;
+    uint32_t refs;        // references of the batch; 0 = nothing to prepare
+    uint32_t R;           // references per pair (K + 2) / per walk position (1 + window * (K + 1))
     int32_t K;
     uint64_t sample_base;
     uint32_t k0, k1;
@@ -103,9 +106,9 @@ struct PrepArgs {
 // runs kPrepUnroll references at once: a block covers 256 * kPrepUnroll consecutive references.
 constexpr int kPrepUnroll = 4;
 
-__device__ __forceinline__ void claim_refs(const PrepArgs& a, unsigned block, unsigned tid)
+__device__ __forceinline__ void claim_pair_refs(const PrepArgs& a, unsigned block, unsigned tid)
 {
-    const uint32_t R = static_cast<uint32_t>(a.K + 2);
+    const uint32_t R = a.R;
     uint32_t t[kPrepUnroll], b[kPrepUnroll];
     int j[kPrepUnroll];
     int32_t id[kPrepUnroll];
@@ -145,25 +148,107 @@ __device__ __forceinline__ void claim_refs(const PrepArgs& a, unsigned block, un
     }
 }
 
+// Walk mode (on-device augmentation, Algorithm 1 "network augmentation"): the batch is a set of
+// walks int32 [n][L]; position i of a walk is the source of the pairs (walk[i], walk[i+j]),
+// 1 <= j <= window, that exist (both entries non-negative, i + j < L).  References of position p:
+//   0                          the source row (vertex table), present if the position has a pair
+//   1 + (j-1)(K+1)             the context row of pair j
+//   1 + (j-1)(K+1) + 1 + k     negative k of pair j, drawn for sample index sample_base + p*window + (j-1)
+// Absent references get id -1 and claim nothing.
+__device__ __forceinline__ void claim_walk_refs(const PrepArgs& a, unsigned block, unsigned tid)
+{
+    const uint32_t R = a.R;
+    const uint32_t L = static_cast<uint32_t>(a.walk_len), W = static_cast<uint32_t>(a.window), K1 = static_cast<uint32_t>(a.K + 1);
+    uint32_t t[kPrepUnroll], p[kPrepUnroll], jj[kPrepUnroll];
+    int kk[kPrepUnroll];     // -2: source, -1: context, >= 0: negative k
+    int32_t id[kPrepUnroll];
+    bool valid[kPrepUnroll];
+    uint4 rnd[kPrepUnroll];
+    uint2 entry[kPrepUnroll];
+    uint64_t draw_slot[kPrepUnroll];
+#pragma unroll
+    for (int u = 0; u < kPrepUnroll; ++u) {
+        t[u] = (block * kPrepUnroll + u) * 256u + tid;
+        id[u] = -1;
+        valid[u] = false;
+        kk[u] = -2;
+        jj[u] = 0;
+        p[u] = 0;
+        if (t[u] < a.refs) {
+            p[u] = t[u] / R;
+            const uint32_t q = t[u] - p[u] * R;
+            const uint32_t r = p[u] / L, i = p[u] - r * L;
+            const int32_t* wk = a.walks + static_cast<int64_t>(r) * L;
+            const int32_t src = wk[i];
+            if (q == 0) {
+                bool has = false;
+                for (uint32_t j = 1; j <= W && i + j < L; ++j) has = has || wk[i + j] >= 0;
+                valid[u] = src >= 0 && has;
+                id[u] = src;
+            } else {
+                jj[u] = (q - 1) / K1;
+                kk[u] = static_cast<int>(q - 1 - jj[u] * K1) - 1;
+                const uint32_t c = i + jj[u] + 1;
+                const int32_t ctx = c < L ? wk[c] : -1;
+                valid[u] = src >= 0 && ctx >= 0;
+                id[u] = ctx;
+                if (valid[u] && kk[u] >= 0) {
+                    const uint64_t sample = a.sample_base + static_cast<uint64_t>(p[u]) * W + jj[u];
+                    rnd[u] = philox4x32_10(make_uint4(static_cast<uint32_t>(sample), static_cast<uint32_t>(sample >> 32),
+                                                      static_cast<uint32_t>(kk[u]), kStreamNegative), a.k0, a.k1);
+                    draw_slot[u] = __umul64hi((static_cast<uint64_t>(rnd[u].x) << 32) | rnd[u].y, a.alias_n);
+                    entry[u] = a.alias[draw_slot[u]];
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kPrepUnroll; ++u) {
+        if (t[u] >= a.refs) continue;
+        if (valid[u] && kk[u] >= 0) {
+            id[u] = a.alias_base + static_cast<int32_t>(rnd[u].z < entry[u].x ? static_cast<uint32_t>(draw_slot[u]) : entry[u].y);
+            if (a.neg_out) a.neg_out[(static_cast<int64_t>(p[u]) * W + jj[u]) * a.K + kk[u]] = id[u];
+        }
+        if (!valid[u]) id[u] = -1;
+        a.ids[t[u]] = id[u];
+        if (valid[u]) {
+            const uint32_t key = static_cast<uint32_t>(id[u]) | (kk[u] == -2 ? 0u : 0x80000000u);
+            a.slots[hash_key(key, a.mask)] = (static_cast<unsigned long long>(key) << 32) | t[u];
+        }
+    }
+}
+
+__device__ __forceinline__ void claim_refs(const PrepArgs& a, unsigned block, unsigned tid)
+{
+    if (a.pairs) claim_pair_refs(a, block, tid);
+    else claim_walk_refs(a, block, tid);
+}
+
 __device__ __forceinline__ void resolve_refs(const PrepArgs& a, unsigned block)
 {
-    const uint32_t R = static_cast<uint32_t>(a.K + 2);
+    const uint32_t R = a.R;
     uint32_t t[kPrepUnroll], key[kPrepUnroll], pos[kPrepUnroll];
+    bool live[kPrepUnroll];   // walk mode leaves holes (id -1) where a walk has no pair
     unsigned long long owner[kPrepUnroll];
 #pragma unroll
     for (int u = 0; u < kPrepUnroll; ++u) {
         t[u] = (block * kPrepUnroll + u) * 256u + threadIdx.x;
         key[u] = 0;
-        if (t[u] < a.refs) key[u] = static_cast<uint32_t>(a.ids[t[u]]) | ((t[u] % R) == 0 ? 0u : 0x80000000u);
+        live[u] = false;
+        if (t[u] < a.refs) {
+            const int32_t id = a.ids[t[u]];
+            live[u] = id >= 0;
+            key[u] = static_cast<uint32_t>(id) | ((t[u] % R) == 0 ? 0u : 0x80000000u);
+        }
     }
 #pragma unroll
     for (int u = 0; u < kPrepUnroll; ++u) {
         pos[u] = hash_key(key[u], a.mask);
-        owner[u] = (t[u] < a.refs) ? a.slots[pos[u]] : 0ull;
+        owner[u] = live[u] ? a.slots[pos[u]] : 0ull;
     }
 #pragma unroll
     for (int u = 0; u < kPrepUnroll; ++u) {
-        if (t[u] >= a.refs) continue;
+        if (!live[u]) continue;
         uint32_t p = pos[u];
         if (static_cast<uint32_t>(owner[u] >> 32) == key[u]) {
             // my row owns its home position; any reference but the one whose store landed last
@@ -208,7 +293,8 @@ __global__ __launch_bounds__(256) void resolve_kernel(PrepArgs a) { resolve_refs
 struct TrainArgs {
     float4* X;
     float4* C;
-    int64_t B;
+    int64_t B;            // pairs (pair mode) / walk positions (walk mode)
+    int32_t window;       // walk mode: pairs per position
     int32_t K;
     int32_t d4;
     float lr;
@@ -229,6 +315,69 @@ __device__ __forceinline__ void to_consecutive(const float4 (&v)[NCH], float (&o
 #pragma unroll
     for (int m = 0; m < 4 * NCH; ++m) out[m] = lds_row[lg + m * G];
     __builtin_amdgcn_wave_barrier();
+}
+
+// The K+1 context rows of one pair (j = 0 the positive, j >= 1 negative j-1), JB at a time: gather,
+// score against x, form g_j, add g_j c_j to dx, and update the row: rewritten in place if only this
+// reference names it, else its delta goes to the row's slot with atomics.  Lane j + LANE0 of the
+// group holds reference j's id, hash position and shared flag.
+template <int G, int NCH, int JB, int LANE0>
+__device__ __forceinline__ void context_rows_of_pair(const TrainArgs& a, int K, int d4, int d, const float4 (&xr)[NCH],
+                                                     const float (&xt)[4 * NCH], float4 (&dx)[NCH], int32_t id_mine,
+                                                     uint32_t pos_mine, int shared_mine, int lg)
+{
+    for (int j0 = 0; j0 <= K; j0 += JB) {
+        float4 cr[JB][NCH];
+        float part[JB];
+        float4* crow[JB];
+#pragma unroll
+        for (int jj = 0; jj < JB; ++jj) {
+            const int j = j0 + jj;
+            const int32_t id = __shfl(id_mine, (j <= K ? j : K) + LANE0, G);
+            crow[jj] = a.C + static_cast<int64_t>(id) * d4;
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) {
+                const int ci = lg + i * G;
+                cr[jj][i] = (j <= K && ci < d4) ? crow[jj][ci] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+#pragma unroll
+        for (int jj = 0; jj < JB; ++jj) {
+            float p = 0.0f;
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) p += dot4(xr[i], cr[jj][i]);
+            part[jj] = p;
+        }
+#pragma unroll
+        for (int jj = 0; jj < JB; ++jj) part[jj] = group_sum<G>(part[jj]);
+#pragma unroll
+        for (int jj = 0; jj < JB; ++jj) {
+            const int j = j0 + jj;
+            if (j <= K) {
+                const float sg = sigmoidf(part[jj]);
+                const float g = a.lr * (j == 0 ? 1.0f - sg : -sg);
+                const int shared = __shfl(shared_mine, j + LANE0, G);
+                const uint32_t pos = __shfl(pos_mine, j + LANE0, G);
+#pragma unroll
+                for (int i = 0; i < NCH; ++i) dx[i] = axpy4(g, cr[jj][i], dx[i]);
+                if (!shared) {
+#pragma unroll
+                    for (int i = 0; i < NCH; ++i) {
+                        const int ci = lg + i * G;
+                        if (ci < d4) crow[jj][ci] = axpy4(g, xr[i], cr[jj][i]);
+                    }
+                } else {
+                    float* slot = a.delta + static_cast<int64_t>(pos) * d;
+#pragma unroll
+                    for (int m = 0; m < 4 * NCH; ++m) {
+                        const int e = lg + m * G;
+                        if (e < d) unsafeAtomicAdd(slot + e, g * xt[m]);
+                    }
+                }
+            }
+        }
+    }
+
 }
 
 #ifndef NE_TRAIN_THREADS
@@ -281,60 +430,90 @@ __global__ __launch_bounds__(kTrainThreads) void train_kernel(TrainArgs a, PrepA
 #pragma unroll
     for (int i = 0; i < NCH; ++i) dx[i] = make_float4(0.f, 0.f, 0.f, 0.f);
 
-    for (int j0 = 0; j0 <= K; j0 += JB) {
-        float4 cr[JB][NCH];
-        float part[JB];
-        float4* crow[JB];
-#pragma unroll
-        for (int jj = 0; jj < JB; ++jj) {
-            const int j = j0 + jj;
-            const int32_t id = __shfl(id_mine, (j <= K ? j : K) + 1, G);
-            crow[jj] = a.C + static_cast<int64_t>(id) * d4;
-#pragma unroll
-            for (int i = 0; i < NCH; ++i) {
-                const int ci = lg + i * G;
-                cr[jj][i] = (j <= K && ci < d4) ? crow[jj][ci] : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-        }
-#pragma unroll
-        for (int jj = 0; jj < JB; ++jj) {
-            float p = 0.0f;
-#pragma unroll
-            for (int i = 0; i < NCH; ++i) p += dot4(xr[i], cr[jj][i]);
-            part[jj] = p;
-        }
-#pragma unroll
-        for (int jj = 0; jj < JB; ++jj) part[jj] = group_sum<G>(part[jj]);
-#pragma unroll
-        for (int jj = 0; jj < JB; ++jj) {
-            const int j = j0 + jj;
-            if (j <= K) {
-                const float sg = sigmoidf(part[jj]);
-                const float g = a.lr * (j == 0 ? 1.0f - sg : -sg);
-                const int shared = __shfl(shared_mine, j + 1, G);
-                const uint32_t pos = __shfl(pos_mine, j + 1, G);
-#pragma unroll
-                for (int i = 0; i < NCH; ++i) dx[i] = axpy4(g, cr[jj][i], dx[i]);
-                if (!shared) {
-#pragma unroll
-                    for (int i = 0; i < NCH; ++i) {
-                        const int ci = lg + i * G;
-                        if (ci < d4) crow[jj][ci] = axpy4(g, xr[i], cr[jj][i]);
-                    }
-                } else {
-                    float* slot = a.delta + static_cast<int64_t>(pos) * d;
-#pragma unroll
-                    for (int m = 0; m < 4 * NCH; ++m) {
-                        const int e = lg + m * G;
-                        if (e < d) unsafeAtomicAdd(slot + e, g * xt[m]);
-                    }
-                }
-            }
-        }
-    }
+    context_rows_of_pair<G, NCH, JB, 1>(a, K, d4, d, xr, xt, dx, id_mine, pos_mine, shared_mine, lg);
 
     const int shared0 = __shfl(shared_mine, 0, G);
     const uint32_t pos0 = __shfl(pos_mine, 0, G);
+    if (!shared0) {
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const int ci = lg + i * G;
+            if (ci < d4)
+                xrow[ci] = make_float4(xr[i].x + dx[i].x, xr[i].y + dx[i].y, xr[i].z + dx[i].z, xr[i].w + dx[i].w);
+        }
+    } else {
+        float dxt[4 * NCH];
+        to_consecutive<G, NCH>(dx, dxt, lds[grp], lg);
+        float* slot = a.delta + static_cast<int64_t>(pos0) * d;
+#pragma unroll
+        for (int m = 0; m < 4 * NCH; ++m) {
+            const int e = lg + m * G;
+            if (e < d) unsafeAtomicAdd(slot + e, dxt[m]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// train kernel of the walk mode: one lane group per walk position.  The source row is gathered once
+// and stays in registers for the position's `window` pairs; its delta is summed over all of them
+// and written once.  Each pair's K+1 context rows are handled exactly as in the pair mode.
+// ---------------------------------------------------------------------------------------------
+template <int G, int NCH, int JB>
+__global__ __launch_bounds__(kTrainThreads) void train_walk_kernel(TrainArgs a, PrepArgs next, unsigned claim_blocks, unsigned period)
+{
+    constexpr int GROUPS = kTrainThreads / G;
+    __shared__ float lds[GROUPS][4 * G * NCH];
+    unsigned block;
+    if (fused_block(claim_blocks, period, &block)) {
+        for (unsigned tid = threadIdx.x; tid < 256u; tid += kTrainThreads) claim_refs(next, block, tid);
+        return;
+    }
+    const int lg = threadIdx.x & (G - 1);
+    const int grp = threadIdx.x / G;
+    const int64_t p = static_cast<int64_t>(block) * GROUPS + grp;
+    if (p >= a.B) return;   // whole groups leave together; groups never communicate below
+    const int K = a.K;
+    const int d4 = a.d4;
+    const int d = d4 * 4;
+    const int64_t R = 1 + static_cast<int64_t>(a.window) * (K + 1);
+    const int64_t ref0 = p * R;
+
+    const int32_t src = a.ids[ref0];
+    if (src < 0) return;    // no pair starts at this position (uniform over the group)
+    const uint32_t pos0 = a.posbuf[ref0];
+    const int shared0 = a.shared[pos0];
+
+    float4* xrow = a.X + static_cast<int64_t>(src) * d4;
+    float4 xr[NCH];
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int ci = lg + i * G;
+        xr[i] = (ci < d4) ? xrow[ci] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    float xt[4 * NCH];   // x in consecutive-dword layout, for the atomic path
+    to_consecutive<G, NCH>(xr, xt, lds[grp], lg);
+
+    float4 dx[NCH];
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) dx[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+
+    for (int j = 0; j < a.window; ++j) {
+        // lane l <= K owns context reference l of pair j
+        int32_t id_mine = -1;
+        uint32_t pos_mine = 0;
+        int shared_mine = 0;
+        if (lg <= K) {
+            const int64_t ref = ref0 + 1 + static_cast<int64_t>(j) * (K + 1) + lg;
+            id_mine = a.ids[ref];
+            if (id_mine >= 0) {
+                pos_mine = a.posbuf[ref];
+                shared_mine = a.shared[pos_mine];
+            }
+        }
+        if (__shfl(id_mine, 0, G) < 0) continue;   // the walk has no pair j here; a pair's references exist together
+        context_rows_of_pair<G, NCH, JB, 0>(a, K, d4, d, xr, xt, dx, id_mine, pos_mine, shared_mine, lg);
+    }
+
     if (!shared0) {
 #pragma unroll
         for (int i = 0; i < NCH; ++i) {
@@ -674,6 +853,22 @@ hipError_t launch_train(const Shape& s, const TrainArgs& a, const PrepArgs& next
     return hipErrorInvalidValue;
 }
 
+hipError_t launch_train_walk(const Shape& s, const TrainArgs& a, const PrepArgs& next, hipStream_t st)
+{
+    const int groups = kTrainThreads / s.G;
+    const unsigned claim_blocks = prep_blocks(next.refs);
+    const unsigned grid = claim_blocks + static_cast<unsigned>((a.B + groups - 1) / groups);
+    const unsigned period = claim_blocks ? grid / claim_blocks : 1u;
+#define NE_CASE(G_, N_)                                                                          \
+    if (s.G == G_ && s.NCH == N_) {                                                              \
+        hipLaunchKernelGGL((train_walk_kernel<G_, N_, 6>), dim3(grid), dim3(kTrainThreads), 0, st, a, next, claim_blocks, period); \
+        return hipGetLastError();                                                                \
+    }
+    NE_FOR_EACH_SHAPE(NE_CASE)
+#undef NE_CASE
+    return hipErrorInvalidValue;
+}
+
 hipError_t launch_loss(const Shape& s, const LossArgs& a, hipStream_t st)
 {
     const int groups = 256 / s.G;
@@ -970,7 +1165,8 @@ ne_status ne_train_block(ne_tables* t, const ne_alias* al, const int32_t* pairs_
         const int64_t Bi = (n_pairs - first < B) ? n_pairs - first : B;
         const PrepSlot& ps = w.prep[i & 1];
         pa.pairs = reinterpret_cast<const int2*>(pairs_dev) + first;
-        pa.refs = static_cast<uint32_t>(Bi * R); pa.K = K; pa.sample_base = sample_base + static_cast<uint64_t>(first);
+        pa.refs = static_cast<uint32_t>(Bi * R); pa.R = static_cast<uint32_t>(R); pa.K = K;
+        pa.sample_base = sample_base + static_cast<uint64_t>(first);
         pa.k0 = static_cast<uint32_t>(t->seed); pa.k1 = static_cast<uint32_t>(t->seed >> 32);
         pa.alias = al ? al->table : nullptr; pa.alias_n = al ? static_cast<uint64_t>(al->n) : 1; pa.alias_base = al ? al->base : 0;
         uint32_t positions = kSweepPerBlock;     // hash positions this batch uses: >= 4 * references
@@ -999,6 +1195,95 @@ ne_status ne_train_block(ne_tables* t, const ne_alias* al, const int32_t* pairs_
         ta.ids = ps.ids; ta.posbuf = ps.posbuf; ta.shared = ps.shared; ta.delta = w.delta;
         const bool timed = profile_begin(t, st);
         e = launch_train(shape, ta, next, st);
+        if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("train launch: ") + hipGetErrorString(e));
+        if (timed) profile_end(t, st);
+
+        ApplyArgs aa{};
+        aa.X = ta.X; aa.C = ta.C; aa.d4 = ta.d4; aa.delta = reinterpret_cast<float4*>(w.delta);
+        aa.positions = cur.mask + 1; aa.slots = ps.slots; aa.shared = ps.shared;
+        const unsigned resolve_blocks = prep_blocks(next.refs);
+        const unsigned sweep_blocks = aa.positions / kSweepPerBlock;
+        const unsigned apply_grid = resolve_blocks + sweep_blocks;
+        hipLaunchKernelGGL(apply_kernel, dim3(apply_grid), dim3(256), 0, st, aa, next, resolve_blocks,
+                           resolve_blocks ? apply_grid / resolve_blocks : 1u);
+        e = hipGetLastError();
+        if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("apply launch: ") + hipGetErrorString(e));
+        t->batches_done += 1;
+        cur = next;
+    }
+    return NE_OK;
+}
+
+ne_status ne_train_walks(ne_tables* t, const ne_alias* al, const int32_t* walks_dev, int64_t n_walks,
+                         int64_t walks_per_batch, int32_t walk_len, int32_t window, int32_t K, const float* lr_host,
+                         uint64_t sample_base, int32_t* neg_out_dev, void* hip_stream)
+{
+    if (!t) return fail(NE_ERR_ARG, "tables handle is NULL");
+    if (K < 0 || K > NE_MAX_NEGATIVES) return fail(NE_ERR_ARG, "K out of range [0, 62]");
+    if (K > 0 && !al) return fail(NE_ERR_ARG, "alias handle is NULL but K > 0");
+    if (walk_len < 2 || walk_len > 65536) return fail(NE_ERR_ARG, "walk_len out of range [2, 65536]");
+    if (window < 1 || window > 64) return fail(NE_ERR_ARG, "window out of range [1, 64]");
+    if (n_walks < 0 || n_walks > (static_cast<int64_t>(1) << 32)) return fail(NE_ERR_ARG, "n_walks out of range");
+    if (al && (al->base < 0 || al->base + al->n > t->num_nodes))
+        return fail(NE_ERR_STATE, "alias id range [base, base+n) is not inside the tables' [0, num_nodes)");
+    Shape shape;
+    if (!pick_shape(t->dim / 4, K, &shape)) return fail(NE_ERR_ARG, "no launch shape for this (dim, K)");
+    if (n_walks == 0) return NE_OK;
+    if (!walks_dev || !aligned(walks_dev, 4)) return fail(NE_ERR_ARG, "walks_dev is NULL or misaligned");
+    if (walks_per_batch < 1) return fail(NE_ERR_ARG, "walks_per_batch must be at least 1");
+    if (!lr_host) return fail(NE_ERR_ARG, "lr_host is NULL");
+    const int64_t n_batches = (n_walks + walks_per_batch - 1) / walks_per_batch;
+    for (int64_t i = 0; i < n_batches; ++i)
+        if (!std::isfinite(lr_host[i])) return fail(NE_ERR_ARG, "lr is not finite");
+    if (t->max_batch <= 0) return fail(NE_ERR_STATE, "tables were created without a training workspace");
+    // the workspace was sized in row references: max_batch * (max_negatives + 2)
+    const int64_t R = 1 + static_cast<int64_t>(window) * (K + 1);
+    const int64_t ref_budget = t->max_batch * (static_cast<int64_t>(t->max_negatives) + 2);
+    const int64_t wpb = walks_per_batch < n_walks ? walks_per_batch : n_walks;
+    if (wpb * walk_len > ref_budget / R)
+        return fail(NE_ERR_ARG, "a batch of walks names more rows than the workspace was sized for: need walks_per_batch * "
+                                "walk_len * (1 + window * (K + 1)) <= max_batch * (max_negatives + 2)");
+
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const Workspace& w = t->ws;
+    const int64_t per_walk = static_cast<int64_t>(walk_len) * window;   // sample indices (and neg_out rows) per walk
+
+    auto prep_args = [&](int64_t i) {
+        PrepArgs pa{};
+        if (i >= n_batches) return pa;   // refs = 0: nothing to prepare
+        const int64_t first = i * walks_per_batch;
+        const int64_t count = (n_walks - first < walks_per_batch) ? n_walks - first : walks_per_batch;
+        const PrepSlot& ps = w.prep[i & 1];
+        pa.walks = walks_dev + first * walk_len; pa.walk_len = walk_len; pa.window = window;
+        pa.refs = static_cast<uint32_t>(count * walk_len * R); pa.R = static_cast<uint32_t>(R); pa.K = K;
+        pa.sample_base = sample_base + static_cast<uint64_t>(first * per_walk);
+        pa.k0 = static_cast<uint32_t>(t->seed); pa.k1 = static_cast<uint32_t>(t->seed >> 32);
+        pa.alias = al ? al->table : nullptr; pa.alias_n = al ? static_cast<uint64_t>(al->n) : 1; pa.alias_base = al ? al->base : 0;
+        uint32_t positions = kSweepPerBlock;     // hash positions this batch uses: >= 4 * references
+        while (positions < 4u * pa.refs) positions <<= 1;
+        pa.slots = ps.slots; pa.mask = positions - 1; pa.shared = ps.shared; pa.ids = ps.ids; pa.posbuf = ps.posbuf;
+        pa.neg_out = neg_out_dev ? neg_out_dev + first * per_walk * K : nullptr;
+        return pa;
+    };
+
+    PrepArgs cur = prep_args(0);
+    const unsigned grid0 = prep_blocks(cur.refs);
+    hipLaunchKernelGGL(claim_kernel, dim3(grid0), dim3(256), 0, st, cur);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("claim launch: ") + hipGetErrorString(e));
+    hipLaunchKernelGGL(resolve_kernel, dim3(grid0), dim3(256), 0, st, cur);
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("resolve launch: ") + hipGetErrorString(e));
+
+    for (int64_t i = 0; i < n_batches; ++i) {
+        const PrepArgs next = prep_args(i + 1);
+        const PrepSlot& ps = w.prep[i & 1];
+        TrainArgs ta{};
+        ta.X = reinterpret_cast<float4*>(t->vertex); ta.C = reinterpret_cast<float4*>(t->context);
+        ta.B = cur.refs / R; ta.window = window; ta.K = K; ta.d4 = t->dim / 4; ta.lr = lr_host[i];
+        ta.ids = ps.ids; ta.posbuf = ps.posbuf; ta.shared = ps.shared; ta.delta = w.delta;
+        const bool timed = profile_begin(t, st);
+        e = launch_train_walk(shape, ta, next, st);
         if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("train launch: ") + hipGetErrorString(e));
         if (timed) profile_end(t, st);
 

@@ -14,6 +14,7 @@ import test_oracle_score as t_score
 import test_oracle_sequential as t_seq
 import test_oracle_sgns as t_sgns
 import test_oracle_shared as t_shared
+import test_oracle_walks as t_walks
 
 SRC = os.path.join(os.path.dirname(oracle.__file__), "ne_oracle.c")
 
@@ -57,6 +58,12 @@ MUTATIONS = [
      "const float* S = second_from_context ? X : C;", [t_score.test_score_hand_values_and_table_choice]),
     ("pair score indexes the second node by the first", "const float* b = S + (int64_t)pairs[2 * i + 1] * d;",
      "const float* b = S + (int64_t)pairs[2 * i] * d;", [t_score.test_score_agrees_with_the_positive_loss_term]),
+    ("walk window one too narrow", "for (int32_t j = 1; j <= window; ++j) {", "for (int32_t j = 1; j < window; ++j) {",
+     [t_walks.test_sample_count_of_full_walks]),
+    ("walk sample direction reversed", "pairs_out[2 * n] = w[i];\n                pairs_out[2 * n + 1] = w[i + j];",
+     "pairs_out[2 * n] = w[i + j];\n                pairs_out[2 * n + 1] = w[i];", [t_walks.test_worked_example]),
+    ("walk sample index without the offset", "* (int64_t)window + (j - 1);", "* (int64_t)window;",
+     [t_walks.test_worked_example]),
 ]
 
 
