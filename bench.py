@@ -101,6 +101,9 @@ def main():
     ap.add_argument("--subparts", type=int, default=0,
                     help="sub-part ping-pong scenario: the vertex rows of one source block live in pinned host memory "
                          "and stream through the device in this many sub-parts while training (c3 shape)")
+    ap.add_argument("--walks", action="store_true",
+                    help="on-device augmentation scenario (walk workloads c1, c2): the same whole-walk batches through "
+                         "ne_train_walks and, expanded to pairs, through ne_train_block")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run 20 plain 1 GiB device copies (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -123,6 +126,9 @@ def main():
         return
     if args.subparts > 0:
         subparts_scenario(args, dev)
+        return
+    if args.walks:
+        walks_scenario(args, dev)
         return
     name = args.workload
     if args.batch > 0:
@@ -233,6 +239,74 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, deg_host, bp, sched, args.cpu_batches)
     print(json.dumps(result), flush=True)
+
+
+def walks_scenario(args, dev):
+    """Walk workloads trained from the walks themselves (ne_train_walks: 4 bytes per walk entry, the source
+    row of an entry gathered once for its window of samples) next to the same batches expanded to pairs
+    (ne_train_block: 8 bytes per sample).  Batches are whole walks, i.e. walk-ordered, not shuffled."""
+    name = args.workload
+    w = WORKLOADS[name]
+    if w["walk"] is None:
+        print("bench.py: --walks needs a walk workload (c1 or c2)", file=sys.stderr)
+        sys.exit(2)
+    V, d, K, B, seed = w["V"], w["d"], w["K"], w["B"], w["seed"]
+    L, win = w["walk"]
+    per_walk = sum(L - j for j in range(1, win + 1))
+    wpb = max(1, B // per_walk)                       # walks per batch: as many whole walks as fit into B samples
+    n_batches = args.steps + args.warmup
+    gdev = "cpu" if V <= 100_000 else dev
+    g = wl.build_graph(V, wl.rmat_edges(V, w["edges"], seed, w["abc"], device=gdev))
+    starts = torch.nonzero(g.degree > 0).reshape(-1)
+    gen = torch.Generator(device=starts.device).manual_seed(seed)
+    starts = starts[torch.randint(0, starts.numel(), (n_batches * wpb,), generator=gen, device=starts.device)]
+    walks = wl.random_walks(g, starts, L, seed).to(torch.int32).to(dev).contiguous()
+    degree = g.degree.to(dev)
+    del g
+    # the same samples as pairs, in the order of the walks (entry, then offset)
+    parts = [torch.stack([walks[:, :-j], walks[:, j:]], dim=2) for j in range(1, win + 1)]      # [n][L-j][2]
+    per_entry = torch.full((walks.shape[0], L, win, 2), -1, dtype=torch.int32, device=dev)
+    for j, part in enumerate(parts, start=1):
+        per_entry[:, :L - j, j - 1, :] = part
+    pairs = per_entry.reshape(walks.shape[0], L * win, 2)
+    pairs = pairs[pairs[:, :, 0] >= 0].reshape(walks.shape[0] * per_walk, 2).contiguous()
+    Bp = wpb * per_walk
+    R = 1 + win * (K + 1)
+    max_B = max(Bp, -(-(wpb * L * R) // (K + 2)))
+    results = {}
+    for mode in ("walks", "pairs"):
+        vertex = torch.empty((V, d), dtype=torch.float32, device=dev)
+        context = torch.empty((V, d), dtype=torch.float32, device=dev)
+        ws = torch.empty(ne.ne_workspace_bytes(d, max_B, K), dtype=torch.uint8, device=dev)
+        tables = ne.ne_create_tables(vertex, context, seed, init=True, max_batch=max_B, max_negatives=K, workspace=ws)
+        at = torch.empty((V, 2), dtype=torch.int32, device=dev)
+        alias = ne.ne_build_neg_alias(degree.clamp(max=2**32 - 1).cpu().numpy().astype(np.uint32), 0, at)
+        lrs = [np.float32(wl.linear_decay_lr(0.025, i * Bp, n_batches * Bp)) for i in range(n_batches)]
+
+        def run(first, last):
+            if mode == "walks":
+                ne.ne_train_walks(tables, alias, walks[first * wpb:last * wpb], wpb, win, K, lrs[first:last], first * wpb * L * win)
+            else:
+                ne.ne_train_block(tables, alias, pairs[first * Bp:last * Bp], Bp, K, lrs[first:last], first * Bp)
+
+        torch.cuda.synchronize()
+        run(0, args.warmup)
+        torch.cuda.synchronize()
+        ne.ne_profile_enable(tables, 4, args.steps // 4 + 2)
+        t0 = time.perf_counter()
+        run(args.warmup, n_batches)
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        kern_ms, kern_n = ne.ne_profile_read(tables)
+        results[mode] = {"pairs_per_s": args.steps * Bp / el, "ms_per_step": el / args.steps * 1e3,
+                         "train_kernel_ms": kern_ms / max(kern_n, 1),
+                         "sample_bytes_per_step": wpb * L * 4 if mode == "walks" else Bp * 8}
+        log(f"walks scenario, {mode}: {results[mode]['pairs_per_s'] / 1e6:.1f} M samples/s, "
+            f"{results[mode]['ms_per_step']:.4f} ms/batch, train kernel {results[mode]['train_kernel_ms'] * 1e3:.1f} us")
+        del tables, vertex, context, ws
+    print(json.dumps({"scenario": "on-device augmentation", "workload": name, "walk_len": L, "window": win,
+                      "walks_per_batch": wpb, "samples_per_batch": Bp, "steps": args.steps, "warmup": args.warmup,
+                      "ne_train_walks": results["walks"], "ne_train_block_same_batches": results["pairs"]}), flush=True)
 
 
 def subparts_scenario(args, dev):
