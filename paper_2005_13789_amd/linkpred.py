@@ -100,16 +100,39 @@ def train(train_edges: np.ndarray, num_nodes: int, dim: int = 64, epochs: int = 
           mode: str = "sync", device: str = "cuda:0"):
     """Embeddings from walks over the training edges: per epoch one walk per node, window pairs shuffled,
     batches of `batch` pairs through ne_train_block (mode "sync", the exact step) or ne_train_batch_async
-    (mode "async"), learning rate decaying linearly over the run.  Returns (Tables, Alias); the handles keep
+    (mode "async"), or the walks themselves through ne_train_walks (mode "walks": the exact step on batches of
+    whole walks, unshuffled), learning rate decaying linearly over the run.  Returns (Tables, Alias); the handles keep
     their device tensors alive (tables.vertex, tables.context)."""
     dev = torch.device(device)
     graph = wl.build_graph(num_nodes, torch.from_numpy(np.asarray(train_edges, dtype=np.int64)))
     vertex = torch.empty((num_nodes, dim), dtype=torch.float32, device=dev)
     context = torch.empty((num_nodes, dim), dtype=torch.float32, device=dev)
-    ws = torch.empty(ne.ne_workspace_bytes(dim, batch, negatives), dtype=torch.uint8, device=dev)
-    tables = ne.ne_create_tables(vertex, context, seed, init=True, max_batch=batch, max_negatives=negatives, workspace=ws)
+    max_batch = batch
+    if mode == "walks":      # references of a batch of whole walks: entries x (1 + window (K + 1))
+        per_walk = sum(walk_length - j for j in range(1, window + 1) if walk_length - j > 0)
+        refs = max(1, batch // max(per_walk, 1)) * walk_length * (1 + window * (negatives + 1))
+        max_batch = max(batch, -(-refs // (negatives + 2)))
+    ws = torch.empty(ne.ne_workspace_bytes(dim, max_batch, negatives), dtype=torch.uint8, device=dev)
+    tables = ne.ne_create_tables(vertex, context, seed, init=True, max_batch=max_batch, max_negatives=negatives, workspace=ws)
     table = torch.empty((num_nodes, 2), dtype=torch.int32, device=dev)
     alias = ne.ne_build_neg_alias(graph.degree.clamp(max=2**32 - 1).numpy().astype(np.uint32), 0, table)
+    if mode == "walks":
+        # on-device augmentation: the walks themselves are the input; a batch is as many whole walks as hold
+        # about `batch` samples
+        per_walk = sum(walk_length - j for j in range(1, window + 1) if walk_length - j > 0)
+        wpb = max(1, batch // max(per_walk, 1))
+        starts = torch.nonzero(graph.degree > 0).reshape(-1)
+        gen = torch.Generator().manual_seed(seed)
+        n_batches = -(-starts.numel() // wpb)
+        for e in range(epochs):
+            order = starts[torch.randperm(starts.numel(), generator=gen)]
+            walks = wl.random_walks(graph, order, walk_length, seed + 1 + e).to(torch.int32).to(dev).contiguous()
+            lrs = np.array([wl.linear_decay_lr(lr0, e * n_batches + b, epochs * n_batches) for b in range(n_batches)],
+                           dtype=np.float32)
+            ne.ne_train_walks(tables, alias, walks, wpb, window, negatives, lrs,
+                              e * starts.numel() * walk_length * window)
+        torch.cuda.synchronize(dev)
+        return tables, alias
     epoch_pairs = [wl.walk_pairs(graph, walk_length, window, None, seed + 1 + e) for e in range(epochs)]
     total = sum(int(p.shape[0]) for p in epoch_pairs)
     done = 0
@@ -124,7 +147,7 @@ def train(train_edges: np.ndarray, num_nodes: int, dim: int = 64, epochs: int = 
             for s, lr in zip(starts, lrs):
                 ne.ne_train_batch_async(tables, alias, p[s:s + batch], negatives, float(lr), done + s)
         else:
-            raise ValueError("mode must be 'sync' or 'async'")
+            raise ValueError("mode must be 'sync', 'async' or 'walks'")
         done += n
     torch.cuda.synchronize(dev)
     return tables, alias
