@@ -262,3 +262,41 @@ def test_config5_whole_batch_on_compacted_rows():
         say(f"  batch {it}: {xs.numel()} + {cs.numel()} touched rows, delta err X {ex:.2e} C {ec:.2e}, loss/pair {loss_o / B:.4f}")
         assert ex <= 2e-4 and ec <= 2e-4
         assert torch.equal(context[probe_c], before_c) and torch.equal(vertex[probe_x], before_x)
+
+
+def test_config2_walk_batches_full_compare():
+    """Config 2's graph trained straight from its walks (ne_train_walks): 3 batches of 170 walks of length 80,
+    window 5, in the fused launch configuration; negatives bit-exact and every table element against the oracle."""
+    say("config 2 graph, walk batches: 1M nodes, 170 walks x 80 per batch, window 5")
+    V, d, K, seed, L, win, wpb, nb = 1_000_000, 128, 5, 1, 80, 5, 170, 3
+    g = wl.build_graph(V, wl.rmat_edges(V, 20_000_000, seed, device=DEV))
+    starts = torch.nonzero(g.degree > 0).reshape(-1)
+    starts = starts[torch.randperm(starts.numel(), generator=torch.Generator(device=DEV).manual_seed(3), device=DEV)[: nb * wpb]]
+    walks = wl.random_walks(g, starts, L, seed).to(torch.int32).contiguous()
+    deg = g.degree.cpu().numpy().astype(np.uint32)
+    del g
+    R = 1 + win * (K + 1)
+    t = make_tables(V, d, K, -(-(wpb * L * R) // (K + 2)), seed)
+    t.context.copy_(torch.randn((V, d), generator=torch.Generator().manual_seed(2)).to(DEV) * 0.05)
+    at = torch.empty((V, 2), dtype=torch.int32, device=DEV)
+    alias = ne.ne_build_neg_alias(deg, 0, at)
+    thr, al, _ = oracle.build_alias(deg)
+    Xo, Co = t.vertex.cpu().numpy(), t.context.cpu().numpy()
+    lrs = [0.025, 0.02, 0.015]
+    neg_out = torch.full((nb * wpb, L, win, K), -1, dtype=torch.int32, device=DEV)
+    ne.ne_train_walks(t, alias, walks, wpb, win, K, lrs, 0, neg_out)
+    torch.cuda.synchronize()
+    wn = walks.cpu().numpy()
+    got = neg_out.cpu().numpy().reshape(-1, K)
+    for b in range(nb):
+        part = np.ascontiguousarray(wn[b * wpb:(b + 1) * wpb])
+        pairs, sample = oracle.walk_pairs(part, win)
+        first = b * wpb * L * win
+        neg_all = oracle.sample_negatives(seed, first, wpb * L * win, K, thr, al)
+        neg = np.ascontiguousarray(neg_all[sample])
+        assert np.array_equal(got[first + sample], neg)
+        oracle.train_batch(Xo, Co, pairs, neg, lrs[b])
+    ex = rowwise_rel_err(t.vertex.cpu().numpy(), Xo, floor_frac=1e-3)
+    ec = rowwise_rel_err(t.context.cpu().numpy(), Co, floor_frac=1e-3)
+    say(f"  rowwise err X {ex:.2e} C {ec:.2e}")
+    assert ex <= 3e-4 and ec <= 3e-4       # three batches
