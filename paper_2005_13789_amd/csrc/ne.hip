@@ -87,7 +87,10 @@ struct PrepArgs {
     const int32_t* walks; // walk mode (pairs == nullptr): the batch's walks, int32 [..][walk_len]
     int32_t walk_len, window;
     uint32_t refs;        // references of the batch; 0 = nothing to prepare
-    uint32_t R;           // references per pair (K + 2) / per walk position (1 + window * (K + 1))
+    uint32_t R;           // references per pair (K + 2) / per walk entry (1 + window * (K + 1)) / per walk segment
+    uint32_t xrefs;       // how many references at the front of each group of R name the vertex table (1; segment mode: entries per segment)
+    uint32_t seg_entries; // walk mode: 0 = one reference group per walk entry; else entries per segment
+    uint32_t segs_per_walk;
     int32_t K;
     uint64_t sample_base;
     uint32_t k0, k1;
@@ -218,9 +221,95 @@ __device__ __forceinline__ void claim_walk_refs(const PrepArgs& a, unsigned bloc
     }
 }
 
+// Walk mode by segments: a walk is cut into segments of E = seg_entries consecutive entries, one
+// workgroup of the train kernel each.  The workgroup sums on chip everything its entries contribute
+// to each other, so a segment names every row once.  References of segment (walk r, entries p0 ..
+// p0+E-1), CT = E + window - 1:
+//   q < E                    vertex row of entry p0 + q, present if that entry starts a sample
+//   E <= q < E + CT          context row of entry p0 + 1 + (q - E), present if one of the segment's
+//                            entries has it as a sample's context (the last window-1 of them belong
+//                            to the next segment's entries too: both segments name them)
+//   E + CT + (e*window + j-1)*K + k   negative k of sample (entry p0 + e, offset j)
+__device__ __forceinline__ void claim_seg_refs(const PrepArgs& a, unsigned block, unsigned tid)
+{
+    const uint32_t R = a.R, E = a.seg_entries;
+    const uint32_t L = static_cast<uint32_t>(a.walk_len), W = static_cast<uint32_t>(a.window), K = static_cast<uint32_t>(a.K);
+    const uint32_t CT = E + W - 1;
+    uint32_t t[kPrepUnroll], samp[kPrepUnroll];
+    int kk[kPrepUnroll];     // -2: vertex row, -1: context row, >= 0: negative k
+    int32_t id[kPrepUnroll];
+    bool valid[kPrepUnroll];
+    uint4 rnd[kPrepUnroll];
+    uint2 entry[kPrepUnroll];
+    uint64_t draw_slot[kPrepUnroll];
+#pragma unroll
+    for (int u = 0; u < kPrepUnroll; ++u) {
+        t[u] = (block * kPrepUnroll + u) * 256u + tid;
+        id[u] = -1;
+        valid[u] = false;
+        kk[u] = -2;
+        samp[u] = 0;
+        if (t[u] < a.refs) {
+            const uint32_t seg = t[u] / R, q = t[u] - seg * R;
+            const uint32_t r = seg / a.segs_per_walk, p0 = (seg - r * a.segs_per_walk) * E;
+            const int32_t* wk = a.walks + static_cast<int64_t>(r) * L;
+            if (q < E) {
+                const uint32_t i = p0 + q;
+                if (i < L) {
+                    bool has = false;
+                    for (uint32_t j = 1; j <= W && i + j < L; ++j) has = has || wk[i + j] >= 0;
+                    id[u] = wk[i];
+                    valid[u] = id[u] >= 0 && has;
+                }
+            } else if (q < E + CT) {
+                kk[u] = -1;
+                const uint32_t c = p0 + 1 + (q - E);
+                if (c < L) {
+                    // sources of this segment that have entry c inside their window
+                    const uint32_t lo = c > p0 + W ? c - W : p0, hi = (c - 1 < p0 + E - 1) ? c - 1 : p0 + E - 1;
+                    bool has = false;
+                    for (uint32_t i = lo; i <= hi; ++i) has = has || wk[i] >= 0;
+                    id[u] = wk[c];
+                    valid[u] = id[u] >= 0 && has;
+                }
+            } else {
+                const uint32_t n = q - E - CT, pj = n / K;    // pj = e * W + (j - 1)
+                kk[u] = static_cast<int>(n - pj * K);
+                const uint32_t e = pj / W, j = pj - e * W + 1, i = p0 + e;
+                if (i + j < L) {
+                    valid[u] = wk[i] >= 0 && wk[i + j] >= 0;
+                    samp[u] = (r * L + i) * W + (j - 1);
+                    if (valid[u]) {
+                        const uint64_t sample = a.sample_base + samp[u];
+                        rnd[u] = philox4x32_10(make_uint4(static_cast<uint32_t>(sample), static_cast<uint32_t>(sample >> 32),
+                                                          static_cast<uint32_t>(kk[u]), kStreamNegative), a.k0, a.k1);
+                        draw_slot[u] = __umul64hi((static_cast<uint64_t>(rnd[u].x) << 32) | rnd[u].y, a.alias_n);
+                        entry[u] = a.alias[draw_slot[u]];
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kPrepUnroll; ++u) {
+        if (t[u] >= a.refs) continue;
+        if (valid[u] && kk[u] >= 0) {
+            id[u] = a.alias_base + static_cast<int32_t>(rnd[u].z < entry[u].x ? static_cast<uint32_t>(draw_slot[u]) : entry[u].y);
+            if (a.neg_out) a.neg_out[static_cast<int64_t>(samp[u]) * a.K + kk[u]] = id[u];
+        }
+        if (!valid[u]) id[u] = -1;
+        a.ids[t[u]] = id[u];
+        if (valid[u]) {
+            const uint32_t key = static_cast<uint32_t>(id[u]) | (kk[u] == -2 ? 0u : 0x80000000u);
+            a.slots[hash_key(key, a.mask)] = (static_cast<unsigned long long>(key) << 32) | t[u];
+        }
+    }
+}
+
 __device__ __forceinline__ void claim_refs(const PrepArgs& a, unsigned block, unsigned tid)
 {
     if (a.pairs) claim_pair_refs(a, block, tid);
+    else if (a.seg_entries) claim_seg_refs(a, block, tid);
     else claim_walk_refs(a, block, tid);
 }
 
@@ -238,7 +327,7 @@ __device__ __forceinline__ void resolve_refs(const PrepArgs& a, unsigned block)
         if (t[u] < a.refs) {
             const int32_t id = a.ids[t[u]];
             live[u] = id >= 0;
-            key[u] = static_cast<uint32_t>(id) | ((t[u] % R) == 0 ? 0u : 0x80000000u);
+            key[u] = static_cast<uint32_t>(id) | ((t[u] % R) < a.xrefs ? 0u : 0x80000000u);
         }
     }
 #pragma unroll
@@ -317,11 +406,11 @@ __device__ __forceinline__ void to_consecutive(const float4 (&v)[NCH], float (&o
     __builtin_amdgcn_wave_barrier();
 }
 
-// The K+1 context rows of one pair (j = 0 the positive, j >= 1 negative j-1), JB at a time: gather,
-// score against x, form g_j, add g_j c_j to dx, and update the row: rewritten in place if only this
-// reference names it, else its delta goes to the row's slot with atomics.  Lane j + LANE0 of the
-// group holds reference j's id, hash position and shared flag.
-template <int G, int NCH, int JB, int LANE0>
+// K+1 context rows of one pair (rows 0..K; with POS_FIRST row 0 is the positive, every other row a
+// negative), JB at a time: gather, score against x, form g_j, add g_j c_j to dx, and update the row:
+// rewritten in place if only this reference names it, else its delta goes to the row's slot with
+// atomics.  Lane j + LANE0 of the group holds reference j's id, hash position and shared flag.
+template <int G, int NCH, int JB, int LANE0, bool POS_FIRST = true>
 __device__ __forceinline__ void context_rows_of_pair(const TrainArgs& a, int K, int d4, int d, const float4 (&xr)[NCH],
                                                      const float (&xt)[4 * NCH], float4 (&dx)[NCH], int32_t id_mine,
                                                      uint32_t pos_mine, int shared_mine, int lg)
@@ -355,7 +444,7 @@ __device__ __forceinline__ void context_rows_of_pair(const TrainArgs& a, int K, 
             const int j = j0 + jj;
             if (j <= K) {
                 const float sg = sigmoidf(part[jj]);
-                const float g = a.lr * (j == 0 ? 1.0f - sg : -sg);
+                const float g = a.lr * ((POS_FIRST && j == 0) ? 1.0f - sg : -sg);
                 const int shared = __shfl(shared_mine, j + LANE0, G);
                 const uint32_t pos = __shfl(pos_mine, j + LANE0, G);
 #pragma unroll
@@ -529,6 +618,185 @@ __global__ __launch_bounds__(kTrainThreads) void train_walk_kernel(TrainArgs a, 
         for (int m = 0; m < 4 * NCH; ++m) {
             const int e = lg + m * G;
             if (e < d) unsafeAtomicAdd(slot + e, dxt[m]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// train kernel of the walk mode by segments: one workgroup per segment of E = threads / G
+// consecutive entries of a walk, one lane group per entry.  All vertex rows of the segment's entries
+// and all context rows that serve as their samples' contexts (E + window - 1 of them) are gathered
+// once into LDS.  Each group then plays two parts:
+//   source   its entry against the up to `window` following context rows (from LDS) and against the
+//            K negatives of each sample (from memory): sums dx in registers, updates the negatives;
+//   context  its entry's context row (and, for the first window-1 groups, one of the rows past the
+//            segment's end) against the vertex rows (from LDS) of the up to `window` preceding
+//            entries of this segment: sums dc in registers.
+// The positive score of a sample is therefore computed twice (both ends need its coefficient); the
+// rows are what costs.  Every row is then written once: in place if no other reference names it,
+// else to its slot with atomics (the context rows next to a segment boundary get contributions
+// from both segments and are always of that kind).
+// ---------------------------------------------------------------------------------------------
+template <int G, int NCH, int JB>
+__global__ __launch_bounds__(kTrainThreads) void train_seg_kernel(TrainArgs a, PrepArgs next, unsigned claim_blocks, unsigned period)
+{
+    constexpr int E = kTrainThreads / G;
+    constexpr int ROW = 4 * G * NCH;              // floats per staged row (>= d)
+    extern __shared__ float seg_lds[];
+    float* scratch = seg_lds;                      // [E][ROW]        layout changes for the atomic path
+    float* xs = scratch + E * ROW;                 // [E][ROW]        vertex rows of the entries
+    float* cs = xs + E * ROW;                      // [E + window - 1][ROW]  context rows
+    const int CT = E + a.window - 1;
+    int32_t* cid = reinterpret_cast<int32_t*>(cs + CT * ROW);   // [CT] ids of the context rows (-1: absent)
+    int32_t* xid = cid + CT;                                    // [E]  ids of the vertex rows (-1: absent)
+    unsigned block;
+    if (fused_block(claim_blocks, period, &block)) {
+        for (unsigned tid = threadIdx.x; tid < 256u; tid += kTrainThreads) claim_refs(next, block, tid);
+        return;
+    }
+    const int lg = threadIdx.x & (G - 1);
+    const int grp = threadIdx.x / G;
+    const int K = a.K;
+    const int W = a.window;
+    const int d4 = a.d4;
+    const int d = d4 * 4;
+    const int64_t R = E + CT + static_cast<int64_t>(E) * W * K;
+    if (static_cast<int64_t>(block) >= a.B) return;             // a.B = segments of the batch (uniform over the workgroup)
+    const int64_t ref0 = static_cast<int64_t>(block) * R;
+
+    // my entry's vertex row, and the context rows grp and grp + E of the segment's list
+    const int32_t src = a.ids[ref0 + grp];
+    uint32_t pos_x = 0;
+    int shared_x = 0;
+    float4 xr[NCH];
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) xr[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    float4* xrow = a.X;
+    if (src >= 0) {
+        pos_x = a.posbuf[ref0 + grp];
+        shared_x = a.shared[pos_x];
+        xrow = a.X + static_cast<int64_t>(src) * d4;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const int ci = lg + i * G;
+            if (ci < d4) xr[i] = xrow[ci];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) reinterpret_cast<float4*>(xs + grp * ROW)[lg + i * G] = xr[i];
+    if (lg == 0) xid[grp] = src;
+    for (int row = grp; row < CT; row += E) {
+        const int32_t id = a.ids[ref0 + E + row];
+        if (lg == 0) cid[row] = id;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const int ci = lg + i * G;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (id >= 0 && ci < d4) v = (a.C + static_cast<int64_t>(id) * d4)[ci];
+            reinterpret_cast<float4*>(cs + row * ROW)[ci] = v;
+        }
+    }
+    __syncthreads();
+
+    // ---- source part
+    if (src >= 0) {
+        float xt[4 * NCH];   // x in consecutive-dword layout, for the atomic path
+        to_consecutive<G, NCH>(xr, xt, scratch + grp * ROW, lg);
+        float4 dx[NCH];
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) dx[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int j = 1; j <= W; ++j) {
+            const int row = grp + j - 1;                      // context row of entry (mine + j)
+            if (cid[row] < 0) continue;                       // no such sample (uniform over the group)
+            float4 cr[NCH];
+            float p = 0.0f;
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) {
+                cr[i] = reinterpret_cast<const float4*>(cs + row * ROW)[lg + i * G];
+                p += dot4(xr[i], cr[i]);
+            }
+            p = group_sum<G>(p);
+            const float g0 = a.lr * (1.0f - sigmoidf(p));
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) dx[i] = axpy4(g0, cr[i], dx[i]);
+            if (K > 0) {
+                // lane k < K owns negative k of this sample
+                int32_t id_mine = -1;
+                uint32_t pos_mine = 0;
+                int shared_mine = 0;
+                if (lg < K) {
+                    const int64_t ref = ref0 + E + CT + (static_cast<int64_t>(grp) * W + (j - 1)) * K + lg;
+                    id_mine = a.ids[ref];
+                    pos_mine = a.posbuf[ref];
+                    shared_mine = a.shared[pos_mine];
+                }
+                context_rows_of_pair<G, NCH, JB, 0, false>(a, K - 1, d4, d, xr, xt, dx, id_mine, pos_mine, shared_mine, lg);
+            }
+        }
+        if (!shared_x) {
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) {
+                const int ci = lg + i * G;
+                if (ci < d4)
+                    xrow[ci] = make_float4(xr[i].x + dx[i].x, xr[i].y + dx[i].y, xr[i].z + dx[i].z, xr[i].w + dx[i].w);
+            }
+        } else {
+            float dxt[4 * NCH];
+            to_consecutive<G, NCH>(dx, dxt, scratch + grp * ROW, lg);
+            float* slot = a.delta + static_cast<int64_t>(pos_x) * d;
+#pragma unroll
+            for (int m = 0; m < 4 * NCH; ++m) {
+                const int e = lg + m * G;
+                if (e < d) unsafeAtomicAdd(slot + e, dxt[m]);
+            }
+        }
+    }
+
+    // ---- context part: context row `row` is entry p0 + 1 + row; its sources in this segment are the
+    // entries with local index max(0, row + 1 - W) .. min(row, E - 1)
+    for (int row = grp; row < CT; row += E) {
+        const int32_t id = cid[row];
+        if (id < 0) continue;
+        float4 cr[NCH], dc[NCH];
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            cr[i] = reinterpret_cast<const float4*>(cs + row * ROW)[lg + i * G];
+            dc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        const int lo = row + 1 - W > 0 ? row + 1 - W : 0, hi = row < E - 1 ? row : E - 1;
+        for (int sl = lo; sl <= hi; ++sl) {
+            if (xid[sl] < 0) continue;
+            float4 xv[NCH];
+            float p = 0.0f;
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) {
+                xv[i] = reinterpret_cast<const float4*>(xs + sl * ROW)[lg + i * G];
+                p += dot4(xv[i], cr[i]);
+            }
+            p = group_sum<G>(p);
+            const float g0 = a.lr * (1.0f - sigmoidf(p));
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) dc[i] = axpy4(g0, xv[i], dc[i]);
+        }
+        const int64_t ref = ref0 + E + row;
+        const uint32_t pos_c = a.posbuf[ref];
+        if (!a.shared[pos_c]) {
+            float4* crow = a.C + static_cast<int64_t>(id) * d4;
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) {
+                const int ci = lg + i * G;
+                if (ci < d4)
+                    crow[ci] = make_float4(cr[i].x + dc[i].x, cr[i].y + dc[i].y, cr[i].z + dc[i].z, cr[i].w + dc[i].w);
+            }
+        } else {
+            float dct[4 * NCH];
+            to_consecutive<G, NCH>(dc, dct, scratch + grp * ROW, lg);
+            float* slot = a.delta + static_cast<int64_t>(pos_c) * d;
+#pragma unroll
+            for (int m = 0; m < 4 * NCH; ++m) {
+                const int e = lg + m * G;
+                if (e < d) unsafeAtomicAdd(slot + e, dct[m]);
+            }
         }
     }
 }
@@ -869,6 +1137,29 @@ hipError_t launch_train_walk(const Shape& s, const TrainArgs& a, const PrepArgs&
     return hipErrorInvalidValue;
 }
 
+// LDS of the segment kernel: scratch, vertex rows and context rows of a segment, and their ids
+size_t seg_lds_bytes(const Shape& s, int window)
+{
+    const size_t E = kTrainThreads / s.G, row = 4 * static_cast<size_t>(s.G) * s.NCH, CT = E + window - 1;
+    return (2 * E + CT) * row * 4 + (CT + E) * 4;
+}
+
+hipError_t launch_train_seg(const Shape& s, const TrainArgs& a, const PrepArgs& next, unsigned segments, hipStream_t st)
+{
+    const unsigned claim_blocks = prep_blocks(next.refs);
+    const unsigned grid = claim_blocks + segments;
+    const unsigned period = claim_blocks ? grid / claim_blocks : 1u;
+    const size_t lds = seg_lds_bytes(s, a.window);
+#define NE_CASE(G_, N_)                                                                          \
+    if (s.G == G_ && s.NCH == N_) {                                                              \
+        hipLaunchKernelGGL((train_seg_kernel<G_, N_, 6>), dim3(grid), dim3(kTrainThreads), lds, st, a, next, claim_blocks, period); \
+        return hipGetLastError();                                                                \
+    }
+    NE_FOR_EACH_SHAPE(NE_CASE)
+#undef NE_CASE
+    return hipErrorInvalidValue;
+}
+
 hipError_t launch_loss(const Shape& s, const LossArgs& a, hipStream_t st)
 {
     const int groups = 256 / s.G;
@@ -1165,7 +1456,7 @@ ne_status ne_train_block(ne_tables* t, const ne_alias* al, const int32_t* pairs_
         const int64_t Bi = (n_pairs - first < B) ? n_pairs - first : B;
         const PrepSlot& ps = w.prep[i & 1];
         pa.pairs = reinterpret_cast<const int2*>(pairs_dev) + first;
-        pa.refs = static_cast<uint32_t>(Bi * R); pa.R = static_cast<uint32_t>(R); pa.K = K;
+        pa.refs = static_cast<uint32_t>(Bi * R); pa.R = static_cast<uint32_t>(R); pa.xrefs = 1; pa.K = K;
         pa.sample_base = sample_base + static_cast<uint64_t>(first);
         pa.k0 = static_cast<uint32_t>(t->seed); pa.k1 = static_cast<uint32_t>(t->seed >> 32);
         pa.alias = al ? al->table : nullptr; pa.alias_n = al ? static_cast<uint64_t>(al->n) : 1; pa.alias_base = al ? al->base : 0;
@@ -1237,12 +1528,22 @@ ne_status ne_train_walks(ne_tables* t, const ne_alias* al, const int32_t* walks_
         if (!std::isfinite(lr_host[i])) return fail(NE_ERR_ARG, "lr is not finite");
     if (t->max_batch <= 0) return fail(NE_ERR_STATE, "tables were created without a training workspace");
     // the workspace was sized in row references: max_batch * (max_negatives + 2)
-    const int64_t R = 1 + static_cast<int64_t>(window) * (K + 1);
+    const int64_t R_entry = 1 + static_cast<int64_t>(window) * (K + 1);
     const int64_t ref_budget = t->max_batch * (static_cast<int64_t>(t->max_negatives) + 2);
     const int64_t wpb = walks_per_batch < n_walks ? walks_per_batch : n_walks;
-    if (wpb * walk_len > ref_budget / R)
+    if (wpb * walk_len > ref_budget / R_entry)
         return fail(NE_ERR_ARG, "a batch of walks names more rows than the workspace was sized for: need walks_per_batch * "
                                 "walk_len * (1 + window * (K + 1)) <= max_batch * (max_negatives + 2)");
+    // One workgroup per segment of E consecutive entries (every row of a segment named once) when a
+    // segment is longer than the window, its rows fit into LDS and the padding of the last segment of
+    // a walk does not cost more references than it saves; else one lane group per entry.
+    const int64_t E = kTrainThreads / shape.G;
+    const int64_t segs_per_walk = (walk_len + E - 1) / E;
+    const int64_t R_seg = E + (E + window - 1) + E * window * K;
+    const bool by_segments = E >= window + 2 && seg_lds_bytes(shape, window) <= 48 * 1024 &&
+                             segs_per_walk * R_seg <= walk_len * R_entry;
+    const int64_t R = by_segments ? R_seg : R_entry;
+    const int64_t groups_per_walk = by_segments ? segs_per_walk : walk_len;   // reference groups (of R) per walk
 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const Workspace& w = t->ws;
@@ -1255,7 +1556,10 @@ ne_status ne_train_walks(ne_tables* t, const ne_alias* al, const int32_t* walks_
         const int64_t count = (n_walks - first < walks_per_batch) ? n_walks - first : walks_per_batch;
         const PrepSlot& ps = w.prep[i & 1];
         pa.walks = walks_dev + first * walk_len; pa.walk_len = walk_len; pa.window = window;
-        pa.refs = static_cast<uint32_t>(count * walk_len * R); pa.R = static_cast<uint32_t>(R); pa.K = K;
+        pa.refs = static_cast<uint32_t>(count * groups_per_walk * R); pa.R = static_cast<uint32_t>(R); pa.K = K;
+        pa.xrefs = by_segments ? static_cast<uint32_t>(E) : 1u;
+        pa.seg_entries = by_segments ? static_cast<uint32_t>(E) : 0u;
+        pa.segs_per_walk = static_cast<uint32_t>(segs_per_walk);
         pa.sample_base = sample_base + static_cast<uint64_t>(first * per_walk);
         pa.k0 = static_cast<uint32_t>(t->seed); pa.k1 = static_cast<uint32_t>(t->seed >> 32);
         pa.alias = al ? al->table : nullptr; pa.alias_n = al ? static_cast<uint64_t>(al->n) : 1; pa.alias_base = al ? al->base : 0;
@@ -1283,7 +1587,7 @@ ne_status ne_train_walks(ne_tables* t, const ne_alias* al, const int32_t* walks_
         ta.B = cur.refs / R; ta.window = window; ta.K = K; ta.d4 = t->dim / 4; ta.lr = lr_host[i];
         ta.ids = ps.ids; ta.posbuf = ps.posbuf; ta.shared = ps.shared; ta.delta = w.delta;
         const bool timed = profile_begin(t, st);
-        e = launch_train_walk(shape, ta, next, st);
+        e = by_segments ? launch_train_seg(shape, ta, next, static_cast<unsigned>(ta.B), st) : launch_train_walk(shape, ta, next, st);
         if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("train launch: ") + hipGetErrorString(e));
         if (timed) profile_end(t, st);
 

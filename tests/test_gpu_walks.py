@@ -51,6 +51,12 @@ def oracle_run(X, C, walks, wpb, window, K, lrs, seed, sample_base, thr, al, bas
     (2000, 32, 0, 30, 9, 2, 30),         # no negatives
     (800, 256, 62, 3, 6, 1, 3),          # the most negatives, window 1
     (100000, 128, 5, 170, 80, 5, 170),   # the shape of config 2: one batch of 170 walks, 65450 samples
+    # walk lengths that fill whole segments of a workgroup's entries: the train kernel then works by segments
+    (5000, 128, 5, 60, 48, 5, 20),
+    (300, 64, 3, 25, 32, 4, 7),          # small graph, segments, nearly every row shared
+    (2000, 32, 0, 30, 64, 2, 30),        # segments without negatives
+    (50000, 128, 5, 40, 80, 14, 40),     # window = entries per segment - 2, the widest that still goes by segments
+    (700, 128, 1, 9, 33, 3, 4),          # one entry past a segment boundary
 ])
 def test_walks_match_oracle(V, d, K, n, L, window, wpb):
     say(f"walks V={V} d={d} K={K} n={n} L={L} window={window} per batch={wpb}")
