@@ -136,8 +136,9 @@ ne_status ne_train_block(ne_tables* tables, const ne_alias* alias, const int32_t
  * sample (walk r, entry i, offset j), r counted over the whole call, are drawn for sample index
  *   sample_base + (r * walk_len + i) * window + (j - 1),
  * so the result does not depend on how the walks are split into batches beyond the batching itself.
- * One lane group handles one walk entry: its vertex row is gathered once for its `window` samples and
- * its delta is written once; walks are 4 bytes per entry where pairs are 8 bytes per sample.
+ * A walk entry's vertex row is gathered once for its `window` samples and its delta written once; where
+ * the shape allows, a workgroup takes a whole segment of consecutive entries and does the same for their
+ * context rows.  Walks are 4 bytes per entry where pairs are 8 bytes per sample.
  *   neg_out_dev : NULL, or device int32 [n_walks][walk_len][window][K]; rows of samples that do not
  *                 exist are left untouched.
  * Needs the training workspace of ne_create_tables with
