@@ -247,22 +247,31 @@ def walks_scenario(args, dev):
     (ne_train_block: 8 bytes per sample).  Batches are whole walks, i.e. walk-ordered, not shuffled."""
     name = args.workload
     w = WORKLOADS[name]
-    if w["walk"] is None:
-        print("bench.py: --walks needs a walk workload (c1 or c2)", file=sys.stderr)
+    if w.get("shared_negatives"):
+        print("bench.py: --walks does not apply to the shared-negative workload", file=sys.stderr)
         sys.exit(2)
     V, d, K, B, seed = w["V"], w["d"], w["K"], w["B"], w["seed"]
-    L, win = w["walk"]
+    L, win = w["walk"] if w["walk"] is not None else (80, 5)
     per_walk = sum(L - j for j in range(1, win + 1))
     wpb = max(1, B // per_walk)                       # walks per batch: as many whole walks as fit into B samples
     n_batches = args.steps + args.warmup
-    gdev = "cpu" if V <= 100_000 else dev
-    g = wl.build_graph(V, wl.rmat_edges(V, w["edges"], seed, w["abc"], device=gdev))
-    starts = torch.nonzero(g.degree > 0).reshape(-1)
-    gen = torch.Generator(device=starts.device).manual_seed(seed)
-    starts = starts[torch.randint(0, starts.numel(), (n_batches * wpb,), generator=gen, device=starts.device)]
-    walks = wl.random_walks(g, starts, L, seed).to(torch.int32).to(dev).contiguous()
-    degree = g.degree.to(dev)
-    del g
+    if w["walk"] is not None:
+        gdev = "cpu" if V <= 100_000 else dev
+        g = wl.build_graph(V, wl.rmat_edges(V, w["edges"], seed, w["abc"], device=gdev))
+        starts = torch.nonzero(g.degree > 0).reshape(-1)
+        gen = torch.Generator(device=starts.device).manual_seed(seed)
+        starts = starts[torch.randint(0, starts.numel(), (n_batches * wpb,), generator=gen, device=starts.device)]
+        walks = wl.random_walks(g, starts, L, seed).to(torch.int32).to(dev).contiguous()
+        degree = g.degree.to(dev)
+        del g
+    else:
+        # Graphs too large to walk here (configs 3, 4): stand-in walks whose entries are drawn like the
+        # endpoints of R-MAT edges (a walk visits nodes in proportion to their degree), inside one block of
+        # the table grid, negatives from that block.  Same row-access statistics, no graph structure.
+        V = V // w["grid"]
+        degree = wl.rmat_degrees(V, w["edges"] // w["grid"] ** 2, seed, w["abc"], device=dev)
+        walks = (wl.rmat_pairs(w["V"], n_batches * wpb * L // 2 + 1, seed, w["abc"], device=dev).reshape(-1)[: n_batches * wpb * L]
+                 % V).to(torch.int32).reshape(n_batches * wpb, L).contiguous()
     # the same samples as pairs, in the order of the walks (entry, then offset)
     parts = [torch.stack([walks[:, :-j], walks[:, j:]], dim=2) for j in range(1, win + 1)]      # [n][L-j][2]
     per_entry = torch.full((walks.shape[0], L, win, 2), -1, dtype=torch.int32, device=dev)
