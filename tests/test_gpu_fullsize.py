@@ -150,7 +150,7 @@ def test_config3_sampled_rows():
 
 
 def test_maximum_batch_size():
-    """One batch of NE_MAX_BATCH pairs (2^22; 29 M row references, 134 M hash positions) through ne_train_batch
+    """One batch of NE_MAX_BATCH pairs (2^22; 29 M row references, 67 M hash positions in use) through ne_train_batch
     and a second one through ne_train_block, every element against the oracle.  A small dimension keeps the
     per-position delta slots (capacity x dim x 4 bytes) and the oracle's time small.  The heavy tail of the
     pairs' id distribution wraps around instead of piling up on one id: with 3.5 % of the pairs sharing one source
