@@ -1096,14 +1096,15 @@ struct Shape { int G, NCH; };
 // Smallest lane group that covers dim/4 float4 chunks and has a lane for each of the K+2 references.
 bool pick_shape(int32_t d4, int32_t K, Shape* out)
 {
-    static const Shape order[] = {{8, 1}, {16, 1}, {16, 2}, {32, 1}, {32, 2}, {64, 1}, {64, 2}, {64, 4}};
+    // one float4 per lane as long as a wavefront holds the row: measured 4-5 % faster at dim 128 than 16 lanes x 2
+    static const Shape order[] = {{8, 1}, {16, 1}, {32, 1}, {64, 1}, {64, 2}, {64, 4}};
     for (const Shape& s : order) {
         if (s.G * s.NCH >= d4 && s.G >= K + 2) { *out = s; return true; }
     }
     return false;
 }
 
-#define NE_FOR_EACH_SHAPE(M) M(8, 1) M(16, 1) M(16, 2) M(32, 1) M(32, 2) M(64, 1) M(64, 2) M(64, 4)
+#define NE_FOR_EACH_SHAPE(M) M(8, 1) M(16, 1) M(32, 1) M(64, 1) M(64, 2) M(64, 4)
 
 hipError_t launch_train(const Shape& s, const TrainArgs& a, const PrepArgs& next, hipStream_t st)
 {
