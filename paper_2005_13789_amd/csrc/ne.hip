@@ -28,6 +28,12 @@
 // claim and resolve never touch the tables, so for a run of batches (ne_train_block) they ride
 // along in the kernels of the batch before: kernel A = train(t) + claim(t+1), kernel B = apply(t) +
 // resolve(t+1), two launches per batch, with two sets of hash state used alternately.
+//
+// The same four phases serve three shapes of batch: pairs (ne_train_batch, ne_train_block), and walks
+// (ne_train_walks: on-device augmentation) by entries or by segments, which differ only in how the
+// references are laid out (claim) and in what a lane group or workgroup keeps on chip (train).
+// Beside the exact step: an unsynchronised per-sample kernel (ne_train_batch_async), the loss and
+// pair-score kernels for evaluation, and table initialisation.
 #include "ne_internal.h"
 
 static thread_local std::string g_last_error;
