@@ -101,6 +101,9 @@ def main():
     ap.add_argument("--subparts", type=int, default=0,
                     help="sub-part ping-pong scenario: the vertex rows of one source block live in pinned host memory "
                          "and stream through the device in this many sub-parts while training (c3 shape)")
+    ap.add_argument("--pinned-pairs", action="store_true",
+                    help="keep the pairs in pinned host memory: ne_train_block_pinned prefetches them inside the training "
+                         "launches (the sample-batch H2D of the paper's pipeline)")
     ap.add_argument("--walks", action="store_true",
                     help="on-device augmentation scenario (walk workloads c1, c2): the same whole-walk batches through "
                          "ne_train_walks and, expanded to pairs, through ne_train_block")
@@ -162,6 +165,10 @@ def main():
     total_pairs = n_batches * B
     lrs = [np.float32(wl.linear_decay_lr(0.025, i * B, total_pairs)) for i in range(n_batches)]
     pairs = bp.pairs
+    pairs_host = None
+    if args.pinned_pairs:
+        pairs_host = pairs.cpu().pin_memory()
+        staging = torch.empty((3, B, 2), dtype=torch.int32, device=dev)
 
     def run(first, last):
         """Batches [first, last).  Consecutive batches of one (src-block, ctx-block) bucket go to the
@@ -183,7 +190,10 @@ def main():
                 while k < last and sched[k][2:] == (bi, bj) and sched[k][0] == sched[k - 1][0] + B:
                     k += 1
             count = k - i
-            ne.ne_train_block(tables, aliases[bj], pairs[s:s + count * B], B, K, lrs[i:k], i * B)
+            if pairs_host is not None:
+                ne.ne_train_block_pinned(tables, aliases[bj], pairs_host[s:s + count * B], B, K, lrs[i:k], i * B, staging)
+            else:
+                ne.ne_train_block(tables, aliases[bj], pairs[s:s + count * B], B, K, lrs[i:k], i * B)
             i = k
 
     torch.cuda.synchronize()
@@ -216,6 +226,8 @@ def main():
                     "traffic": TRAFFIC_BYTES_PER_LAUNCH[name] if args.mode == "sync" else None, "bytes_per_launch": bpp * B,
                     "avg_kernel_ms": avg_kernel_ms, "kernel_samples": kern_n}
         call = "ne_train_batch per step" if args.per_batch else "ne_train_block per bucket run"
+        if pairs_host is not None:
+            call = "ne_train_block_pinned per bucket run (pairs prefetched from pinned host memory inside the launches)"
         if args.mode == "async":
             call = "ne_train_batch_async per step (unsynchronised mode, not the exact step)"
     result = {

@@ -126,6 +126,24 @@ ne_status ne_train_block(ne_tables* tables, const ne_alias* alias, const int32_t
                          uint64_t sample_base, int32_t* neg_out_dev, void* hip_stream);
 
 /*
+ * ne_train_block on samples that stay in pinned host memory (the paper's training pipeline, Sec. IV-A:
+ * the host-to-device copy of the next sample batches is hidden behind training).  Same batches, same
+ * result as ne_train_block; the pairs of batch i+2 are copied into a ring of three batch buffers by a few
+ * helper workgroups inside the launch that trains batch i, so no second stream and no event is involved
+ * (copies on a second stream ordered by events, whether memcpys or kernels, were measured to cost 6-25 % of
+ * the training rate; riding along costs 3 %).
+ *   pairs_host_pinned : host, page-locked, int32[n_pairs][2], 8-byte aligned; must stay valid and
+ *                       unchanged until the enqueued work is done.
+ *   staging_dev       : device, int32[3][B][2], 16-byte aligned, caller-owned scratch.
+ * Other arguments, semantics and errors as for ne_train_block; NE_ERR_ARG also when the host buffer is not
+ * page-locked.
+ */
+ne_status ne_train_block_pinned(ne_tables* tables, const ne_alias* alias, const int32_t* pairs_host_pinned,
+                                int64_t n_pairs, int64_t B, int32_t K, const float* lr_host,
+                                uint64_t sample_base, int32_t* staging_dev, int32_t* neg_out_dev,
+                                void* hip_stream);
+
+/*
  * On-device augmentation (Algorithm 1, "network augmentation"; Sec. IV-A variant that merges the
  * augmentation into a later stage): trains directly on random walks instead of on materialised pairs.
  * walks_dev is int32 [n_walks][walk_len] (device); entry i of a walk is the source of the samples

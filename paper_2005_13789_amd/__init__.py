@@ -25,7 +25,7 @@ NE_MAX_NEGATIVES = 62
 NE_MAX_BATCH = 1 << 22
 
 EXPORTS = (
-    "ne_create_tables", "ne_build_neg_alias", "ne_workspace_bytes", "ne_train_batch", "ne_train_block", "ne_train_walks",
+    "ne_create_tables", "ne_build_neg_alias", "ne_workspace_bytes", "ne_train_batch", "ne_train_block", "ne_train_block_pinned", "ne_train_walks",
     "ne_shared_workspace_bytes", "ne_train_batch_shared", "ne_train_batch_async", "ne_set_vertex_window", "ne_eval_loss",
     "ne_score_pairs", "ne_validate_pairs", "ne_profile_enable", "ne_profile_read", "ne_destroy_tables", "ne_destroy_alias", "ne_last_error",
 )
@@ -61,6 +61,9 @@ def lib() -> ctypes.CDLL:
     L.ne_train_batch.restype = c.c_int
     L.ne_train_block.argtypes = [vp, vp, vp, c.c_int64, c.c_int64, c.c_int32, c.POINTER(c.c_float), c.c_uint64, vp, vp]
     L.ne_train_block.restype = c.c_int
+    L.ne_train_block_pinned.argtypes = [vp, vp, vp, c.c_int64, c.c_int64, c.c_int32, c.POINTER(c.c_float), c.c_uint64, vp,
+                                        vp, vp]
+    L.ne_train_block_pinned.restype = c.c_int
     L.ne_shared_workspace_bytes.argtypes = [c.c_int32, c.c_int64, c.c_int32]
     L.ne_shared_workspace_bytes.restype = c.c_size_t
     L.ne_train_batch_shared.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_float, c.c_float, c.c_uint64, vp,
@@ -211,6 +214,27 @@ def ne_train_block(tables: Tables, alias: Alias | None, pairs: torch.Tensor, B: 
         raise TypeError("neg_out needs n_pairs*K int32 elements")
     _check(lib().ne_train_block(tables.handle, alias.handle if alias else None, pp, n_pairs, B, K, arr, sample_base,
                                 np_, _stream_ptr(stream)))
+
+
+def ne_train_block_pinned(tables: Tables, alias: Alias | None, pairs_host: torch.Tensor, B: int, K: int, lrs,
+                          sample_base: int, staging: torch.Tensor, neg_out: torch.Tensor | None = None, stream=None) -> None:
+    """ne_train_block on pairs in pinned CPU memory (int32 [n][2]); staging: CUDA int32 [3][B][2]."""
+    if not (isinstance(pairs_host, torch.Tensor) and not pairs_host.is_cuda and pairs_host.dtype == torch.int32
+            and pairs_host.is_contiguous() and pairs_host.is_pinned()):
+        raise TypeError("pairs_host: need a contiguous pinned CPU tensor of torch.int32")
+    n_pairs = int(pairs_host.shape[0])
+    n_batches = -(-n_pairs // B) if B > 0 else 0
+    if len(lrs) < n_batches:
+        raise TypeError("lrs needs one learning rate per batch")
+    arr = (ctypes.c_float * max(n_batches, 1))(*[float(v) for v in lrs[:n_batches]])
+    sp = _dev_ptr(staging, torch.int32, "staging")
+    if staging.numel() < 6 * B:
+        raise ValueError("staging needs 3*B*2 int32 elements")
+    np_ = _dev_ptr(neg_out, torch.int32, "neg_out")
+    if neg_out is not None and neg_out.numel() < n_pairs * K:
+        raise TypeError("neg_out needs n_pairs*K int32 elements")
+    _check(lib().ne_train_block_pinned(tables.handle, alias.handle if alias else None, pairs_host.data_ptr(), n_pairs, B, K,
+                                       arr, sample_base, sp, np_, _stream_ptr(stream)))
 
 
 def ne_train_walks(tables: Tables, alias: Alias | None, walks: torch.Tensor, walks_per_batch: int, window: int, K: int,

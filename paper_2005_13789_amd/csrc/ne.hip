@@ -109,6 +109,12 @@ struct PrepArgs {
     int32_t* ids;
     uint32_t* posbuf;
     int32_t* neg_out;
+    // sample prefetch riding along (ne_train_block_pinned): fetch_blocks helper workgroups copy fetch_n
+    // pairs from pinned host memory (fetch_src: its device address) into the staging ring (fetch_dst)
+    const int2* fetch_src;
+    int2* fetch_dst;
+    int64_t fetch_n;
+    uint32_t fetch_blocks;
 };
 
 // Both phases are chains of dependent memory accesses with next to no arithmetic, so each thread
@@ -367,6 +373,39 @@ __device__ __forceinline__ void resolve_refs(const PrepArgs& a, unsigned block)
 // Number of blocks either phase needs for `refs` references.
 inline unsigned prep_blocks(uint32_t refs) { return (refs + 256u * kPrepUnroll - 1u) / (256u * kPrepUnroll); }
 
+// ---------------------------------------------------------------------------------------------
+// sample prefetch (ne_train_block_pinned): a few workgroups copy the pairs of a later batch from
+// pinned host memory, which they read directly, into a device staging ring.  They ride inside the
+// training launches; the first two batches of a call use the stand-alone kernel.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void fetch_pairs(const int2* __restrict__ src, int2* __restrict__ dst, int64_t n, int64_t i0,
+                                            int64_t stride)
+{
+    // pairs two at a time while both buffers allow 16-byte accesses
+    const bool wide = ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15) == 0;
+    if (wide) {
+        const int64_t n2 = n / 2;
+        const int4* s4 = reinterpret_cast<const int4*>(src);
+        int4* d4 = reinterpret_cast<int4*>(dst);
+        // four loads in flight per thread: the link's latency is long and the copy should stay small
+        int64_t i = i0;
+        for (; i + 3 * stride < n2; i += 4 * stride) {
+            const int4 v0 = s4[i], v1 = s4[i + stride], v2 = s4[i + 2 * stride], v3 = s4[i + 3 * stride];
+            d4[i] = v0; d4[i + stride] = v1; d4[i + 2 * stride] = v2; d4[i + 3 * stride] = v3;
+        }
+        for (; i < n2; i += stride) d4[i] = s4[i];
+        if (i0 == 0 && (n & 1)) dst[n - 1] = src[n - 1];
+    } else {
+        for (int64_t i = i0; i < n; i += stride) dst[i] = src[i];
+    }
+}
+
+__global__ __launch_bounds__(256) void fetch_pairs_kernel(const int2* __restrict__ src, int2* __restrict__ dst, int64_t n)
+{
+    fetch_pairs(src, dst, n, static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x,
+                static_cast<int64_t>(gridDim.x) * blockDim.x);
+}
+
 // Placement of `extra` helper blocks among `total` blocks of a fused launch: every period-th block is
 // a helper until they run out, so helpers and main blocks are resident together from the start.
 __device__ __forceinline__ bool fused_block(unsigned extra, unsigned period, unsigned* index)
@@ -488,6 +527,12 @@ __global__ __launch_bounds__(kTrainThreads) void train_kernel(TrainArgs a, PrepA
     // some blocks do the id-only claim phase of the next batch
     unsigned block;
     if (fused_block(claim_blocks, period, &block)) {
+        if (block < next.fetch_blocks) {   // sample prefetch for the batch after the next
+            fetch_pairs(next.fetch_src, next.fetch_dst, next.fetch_n, static_cast<int64_t>(block) * kTrainThreads + threadIdx.x,
+                        static_cast<int64_t>(next.fetch_blocks) * kTrainThreads);
+            return;
+        }
+        block -= next.fetch_blocks;
         for (unsigned tid = threadIdx.x; tid < 256u; tid += kTrainThreads) claim_refs(next, block, tid);
         return;
     }
@@ -560,6 +605,12 @@ __global__ __launch_bounds__(kTrainThreads) void train_walk_kernel(TrainArgs a, 
     __shared__ float lds[GROUPS][4 * G * NCH];
     unsigned block;
     if (fused_block(claim_blocks, period, &block)) {
+        if (block < next.fetch_blocks) {   // sample prefetch for the batch after the next
+            fetch_pairs(next.fetch_src, next.fetch_dst, next.fetch_n, static_cast<int64_t>(block) * kTrainThreads + threadIdx.x,
+                        static_cast<int64_t>(next.fetch_blocks) * kTrainThreads);
+            return;
+        }
+        block -= next.fetch_blocks;
         for (unsigned tid = threadIdx.x; tid < 256u; tid += kTrainThreads) claim_refs(next, block, tid);
         return;
     }
@@ -657,6 +708,12 @@ __global__ __launch_bounds__(kTrainThreads) void train_seg_kernel(TrainArgs a, P
     int32_t* xid = cid + CT;                                    // [E]  ids of the vertex rows (-1: absent)
     unsigned block;
     if (fused_block(claim_blocks, period, &block)) {
+        if (block < next.fetch_blocks) {   // sample prefetch for the batch after the next
+            fetch_pairs(next.fetch_src, next.fetch_dst, next.fetch_n, static_cast<int64_t>(block) * kTrainThreads + threadIdx.x,
+                        static_cast<int64_t>(next.fetch_blocks) * kTrainThreads);
+            return;
+        }
+        block -= next.fetch_blocks;
         for (unsigned tid = threadIdx.x; tid < 256u; tid += kTrainThreads) claim_refs(next, block, tid);
         return;
     }
@@ -1115,7 +1172,7 @@ bool pick_shape(int32_t d4, int32_t K, Shape* out)
 hipError_t launch_train(const Shape& s, const TrainArgs& a, const PrepArgs& next, hipStream_t st)
 {
     const int groups = kTrainThreads / s.G;
-    const unsigned claim_blocks = prep_blocks(next.refs);
+    const unsigned claim_blocks = prep_blocks(next.refs) + next.fetch_blocks;   // helper workgroups
     const unsigned grid = claim_blocks + static_cast<unsigned>((a.B + groups - 1) / groups);
     const unsigned period = claim_blocks ? grid / claim_blocks : 1u;
 #define NE_CASE(G_, N_)                                                                          \
@@ -1131,7 +1188,7 @@ hipError_t launch_train(const Shape& s, const TrainArgs& a, const PrepArgs& next
 hipError_t launch_train_walk(const Shape& s, const TrainArgs& a, const PrepArgs& next, hipStream_t st)
 {
     const int groups = kTrainThreads / s.G;
-    const unsigned claim_blocks = prep_blocks(next.refs);
+    const unsigned claim_blocks = prep_blocks(next.refs) + next.fetch_blocks;   // helper workgroups
     const unsigned grid = claim_blocks + static_cast<unsigned>((a.B + groups - 1) / groups);
     const unsigned period = claim_blocks ? grid / claim_blocks : 1u;
 #define NE_CASE(G_, N_)                                                                          \
@@ -1153,7 +1210,7 @@ size_t seg_lds_bytes(const Shape& s, int window)
 
 hipError_t launch_train_seg(const Shape& s, const TrainArgs& a, const PrepArgs& next, unsigned segments, hipStream_t st)
 {
-    const unsigned claim_blocks = prep_blocks(next.refs);
+    const unsigned claim_blocks = prep_blocks(next.refs) + next.fetch_blocks;   // helper workgroups
     const unsigned grid = claim_blocks + segments;
     const unsigned period = claim_blocks ? grid / claim_blocks : 1u;
     const size_t lds = seg_lds_bytes(s, a.window);
@@ -1203,6 +1260,8 @@ constexpr int64_t kMaxBatch = static_cast<int64_t>(1) << 22;
 // (load <= 1/2) halves the sweep and the footprint of the delta slots, which measured more than
 // pays for the extra probing (1 M nodes, 458 752 references: +8 %; 100 M nodes: -3 %).
 constexpr uint32_t kHashFactorMax = 4;
+// helper workgroups that prefetch the samples of a later batch from pinned host memory (512 KB per batch of 65536)
+constexpr unsigned kFetchBlocks = 8;
 inline uint32_t hash_factor(int64_t num_nodes, uint32_t refs) { return num_nodes <= 16 * static_cast<int64_t>(refs) ? 2u : 4u; }
 
 bool workspace_layout(int32_t dim, int64_t max_B, int32_t max_K, char* base, Workspace* w)
@@ -1441,9 +1500,11 @@ ne_status ne_build_neg_alias(ne_alias** out, const uint32_t* degree_host, int64_
     return NE_OK;
 }
 
-ne_status ne_train_block(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t n_pairs, int64_t B,
-                         int32_t K, const float* lr_host, uint64_t sample_base, int32_t* neg_out_dev,
-                         void* hip_stream)
+// pairs_dev: the samples on the device; or, with staging != nullptr, the device address of the samples in
+// pinned host memory, which are then prefetched batch by batch into the ring staging[3][B].
+static ne_status train_block_impl(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t n_pairs, int64_t B,
+                                  int32_t K, const float* lr_host, uint64_t sample_base, int32_t* neg_out_dev,
+                                  int2* staging, void* hip_stream)
 {
     Shape shape;
     ne_status rc = check_batch_args(t, al, pairs_dev, B, K, &shape);
@@ -1469,7 +1530,15 @@ ne_status ne_train_block(ne_tables* t, const ne_alias* al, const int32_t* pairs_
         const int64_t first = i * B;
         const int64_t Bi = (n_pairs - first < B) ? n_pairs - first : B;
         const PrepSlot& ps = w.prep[i & 1];
-        pa.pairs = reinterpret_cast<const int2*>(pairs_dev) + first;
+        pa.pairs = staging ? staging + (i % 3) * B : reinterpret_cast<const int2*>(pairs_dev) + first;
+        if (staging && i + 1 < n_batches) {
+            // the launch that trains batch i - 1 and claims batch i also fetches batch i + 1
+            const int64_t f = (i + 1) * B;
+            pa.fetch_src = reinterpret_cast<const int2*>(pairs_dev) + f;
+            pa.fetch_dst = staging + ((i + 1) % 3) * B;
+            pa.fetch_n = (n_pairs - f < B) ? n_pairs - f : B;
+            pa.fetch_blocks = kFetchBlocks;
+        }
         pa.refs = static_cast<uint32_t>(Bi * R); pa.R = static_cast<uint32_t>(R); pa.xrefs = 1; pa.K = K;
         pa.sample_base = sample_base + static_cast<uint64_t>(first);
         pa.k0 = static_cast<uint32_t>(t->seed); pa.k1 = static_cast<uint32_t>(t->seed >> 32);
@@ -1481,8 +1550,18 @@ ne_status ne_train_block(ne_tables* t, const ne_alias* al, const int32_t* pairs_
         return pa;
     };
 
+    if (staging) {   // batches 0 and 1 have no launch to ride along with
+        for (int64_t i = 0; i < 2 && i < n_batches; ++i) {
+            const int64_t f = i * B, cnt = (n_pairs - f < B) ? n_pairs - f : B;
+            hipLaunchKernelGGL(fetch_pairs_kernel, dim3(kFetchBlocks), dim3(256), 0, st,
+                               reinterpret_cast<const int2*>(pairs_dev) + f, staging + (i % 3) * B, cnt);
+            hipError_t fe = hipGetLastError();
+            if (fe != hipSuccess) return fail(NE_ERR_HIP, std::string("fetch launch: ") + hipGetErrorString(fe));
+        }
+    }
     // the first batch has no predecessor to ride along with
     PrepArgs cur = prep_args(0);
+    cur.fetch_blocks = 0;   // batch 1 was fetched above
     const unsigned grid0 = prep_blocks(cur.refs);
     hipLaunchKernelGGL(claim_kernel, dim3(grid0), dim3(256), 0, st, cur);
     hipError_t e = hipGetLastError();
@@ -1517,6 +1596,33 @@ ne_status ne_train_block(ne_tables* t, const ne_alias* al, const int32_t* pairs_
         cur = next;
     }
     return NE_OK;
+}
+
+ne_status ne_train_block(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t n_pairs, int64_t B,
+                         int32_t K, const float* lr_host, uint64_t sample_base, int32_t* neg_out_dev,
+                         void* hip_stream)
+{
+    return train_block_impl(t, al, pairs_dev, n_pairs, B, K, lr_host, sample_base, neg_out_dev, nullptr, hip_stream);
+}
+
+ne_status ne_train_block_pinned(ne_tables* t, const ne_alias* al, const int32_t* pairs_host_pinned, int64_t n_pairs,
+                                int64_t B, int32_t K, const float* lr_host, uint64_t sample_base, int32_t* staging_dev,
+                                int32_t* neg_out_dev, void* hip_stream)
+{
+    if (n_pairs > 0 && B >= 1) {
+        if (!pairs_host_pinned || !aligned(pairs_host_pinned, 8)) return fail(NE_ERR_ARG, "pairs_host_pinned is NULL or not 8-byte aligned");
+        if (!staging_dev || !aligned(staging_dev, 16)) return fail(NE_ERR_ARG, "staging_dev is NULL or not 16-byte aligned");
+    }
+    void* src_dev = const_cast<int32_t*>(pairs_host_pinned);
+    if (pairs_host_pinned) {
+        hipError_t e = hipHostGetDevicePointer(&src_dev, const_cast<int32_t*>(pairs_host_pinned), 0);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(NE_ERR_ARG, std::string("pairs_host_pinned is not pinned (page-locked) host memory: ") + hipGetErrorString(e));
+        }
+    }
+    return train_block_impl(t, al, static_cast<const int32_t*>(src_dev), n_pairs, B, K, lr_host, sample_base, neg_out_dev,
+                            reinterpret_cast<int2*>(staging_dev), hip_stream);
 }
 
 ne_status ne_train_walks(ne_tables* t, const ne_alias* al, const int32_t* walks_dev, int64_t n_walks,
