@@ -227,6 +227,11 @@ struct ScoresArgs {
     const int2* pairs;
 };
 
+// Column of G inside its LDS row: the eight 16-byte groups of a row are permuted by the row's 16-row
+// block, so that the transposed read-out below (one negative, rows 16 apart) spreads over the banks
+// while a fragment read (one row, 8 consecutive negatives) stays one 16-byte access.
+__device__ __forceinline__ int g_col(int row, int col) { return ((((col >> 3) ^ (row >> 4)) & 7) << 3) | (col & 7); }
+
 template <int D>
 __global__ __launch_bounds__(kScoreThreads) void scores_kernel(ScoresArgs a)
 {
@@ -344,7 +349,7 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(ScoresArgs a)
             const bool valid = b0 + row < a.B;
             const float g = valid ? -a.neg_scale * fast_sigmoidf(s[i]) : 0.0f;
             if (a.loss && valid) loss += a.neg_scale * softplusf(s[i]);
-            Gs[row * TP + col] = to_bf16(g);
+            Gs[row * TP + g_col(row, col)] = to_bf16(g);
         }
         __syncthreads();
 
@@ -354,16 +359,17 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(ScoresArgs a)
             uint32_t p[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                p[i] = Gs[(part * 16 + 2 * i) * TP + neg] | (static_cast<uint32_t>(Gs[(part * 16 + 2 * i + 1) * TP + neg]) << 16);
+                p[i] = Gs[(part * 16 + 2 * i) * TP + g_col(part * 16, neg)] |
+                       (static_cast<uint32_t>(Gs[(part * 16 + 2 * i + 1) * TP + g_col(part * 16, neg)]) << 16);
             uint4* out = reinterpret_cast<uint4*>(a.w.GT + static_cast<int64_t>(n0 + neg) * Bp + b0 + part * 16);
             out[0] = make_uint4(p[0], p[1], p[2], p[3]);
             out[1] = make_uint4(p[4], p[5], p[6], p[7]);
         }
         // dX += G . Cq for 32 pairs x D/2 columns over the 64 negatives of the chunk
-        const uint16_t* ga = Gs + (rh * 32 + (l & 31)) * TP + (l >> 5) * 8;
+        const uint16_t* ga = Gs + (rh * 32 + (l & 31)) * TP;
 #pragma unroll
         for (int kk = 0; kk < kNegChunk; kk += 16) {
-            const bf16x8 av = as_bf16x8(*reinterpret_cast<const uint4*>(ga + kk));
+            const bf16x8 av = as_bf16x8(*reinterpret_cast<const uint4*>(ga + g_col(rh * 32 + (l & 31), kk + (l >> 5) * 8)));
 #pragma unroll
             for (int t = 0; t < DT; ++t) {
                 const uint16_t* tb = CTs + (ch * (D / 2) + t * 32 + (l & 31)) * TP + (l >> 5) * 8 + kk;
