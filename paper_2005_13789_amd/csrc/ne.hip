@@ -1311,6 +1311,53 @@ ne_status check_batch_args(const ne_tables* t, const ne_alias* al, const int32_t
     return NE_OK;
 }
 
+// The launches of a run of batches, common to the pair and the walk shapes: claim and resolve of the
+// first batch stand alone; then per batch kernel A = train(i) + claim(i+1) (+ sample prefetch) and
+// kernel B = apply(i) + resolve(i+1).  prep(i) describes batch i (refs = 0 past the end); train(ta, next)
+// launches the shape's train kernel.
+template <class PrepFn, class TrainFn>
+ne_status run_batches(ne_tables* t, int64_t n_batches, int64_t R, int32_t window, int32_t K, const float* lr_host,
+                             hipStream_t st, PrepFn prep, TrainFn train)
+{
+    const Workspace& w = t->ws;
+    PrepArgs cur = prep(0);
+    cur.fetch_blocks = 0;   // a prefetch only rides in train launches
+    const unsigned grid0 = prep_blocks(cur.refs);
+    hipLaunchKernelGGL(claim_kernel, dim3(grid0), dim3(256), 0, st, cur);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("claim launch: ") + hipGetErrorString(e));
+    hipLaunchKernelGGL(resolve_kernel, dim3(grid0), dim3(256), 0, st, cur);
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("resolve launch: ") + hipGetErrorString(e));
+
+    for (int64_t i = 0; i < n_batches; ++i) {
+        const PrepArgs next = prep(i + 1);
+        const PrepSlot& ps = w.prep[i & 1];
+        TrainArgs ta{};
+        ta.X = reinterpret_cast<float4*>(t->vertex); ta.C = reinterpret_cast<float4*>(t->context);
+        ta.B = cur.refs / R; ta.window = window; ta.K = K; ta.d4 = t->dim / 4; ta.lr = lr_host[i];
+        ta.ids = ps.ids; ta.posbuf = ps.posbuf; ta.shared = ps.shared; ta.delta = w.delta;
+        const bool timed = profile_begin(t, st);
+        e = train(ta, next);
+        if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("train launch: ") + hipGetErrorString(e));
+        if (timed) profile_end(t, st);
+
+        ApplyArgs aa{};
+        aa.X = ta.X; aa.C = ta.C; aa.d4 = ta.d4; aa.delta = reinterpret_cast<float4*>(w.delta);
+        aa.positions = cur.mask + 1; aa.slots = ps.slots; aa.shared = ps.shared;
+        const unsigned resolve_blocks = prep_blocks(next.refs);
+        const unsigned sweep_blocks = aa.positions / kSweepPerBlock;
+        const unsigned apply_grid = resolve_blocks + sweep_blocks;
+        hipLaunchKernelGGL(apply_kernel, dim3(apply_grid), dim3(256), 0, st, aa, next, resolve_blocks,
+                           resolve_blocks ? apply_grid / resolve_blocks : 1u);
+        e = hipGetLastError();
+        if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("apply launch: ") + hipGetErrorString(e));
+        t->batches_done += 1;
+        cur = next;
+    }
+    return NE_OK;
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
@@ -1559,43 +1606,8 @@ static ne_status train_block_impl(ne_tables* t, const ne_alias* al, const int32_
             if (fe != hipSuccess) return fail(NE_ERR_HIP, std::string("fetch launch: ") + hipGetErrorString(fe));
         }
     }
-    // the first batch has no predecessor to ride along with
-    PrepArgs cur = prep_args(0);
-    cur.fetch_blocks = 0;   // batch 1 was fetched above
-    const unsigned grid0 = prep_blocks(cur.refs);
-    hipLaunchKernelGGL(claim_kernel, dim3(grid0), dim3(256), 0, st, cur);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("claim launch: ") + hipGetErrorString(e));
-    hipLaunchKernelGGL(resolve_kernel, dim3(grid0), dim3(256), 0, st, cur);
-    e = hipGetLastError();
-    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("resolve launch: ") + hipGetErrorString(e));
-
-    for (int64_t i = 0; i < n_batches; ++i) {
-        const PrepArgs next = prep_args(i + 1);
-        const PrepSlot& ps = w.prep[i & 1];
-        TrainArgs ta{};
-        ta.X = reinterpret_cast<float4*>(t->vertex); ta.C = reinterpret_cast<float4*>(t->context);
-        ta.B = cur.refs / R; ta.K = K; ta.d4 = t->dim / 4; ta.lr = lr_host[i];
-        ta.ids = ps.ids; ta.posbuf = ps.posbuf; ta.shared = ps.shared; ta.delta = w.delta;
-        const bool timed = profile_begin(t, st);
-        e = launch_train(shape, ta, next, st);
-        if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("train launch: ") + hipGetErrorString(e));
-        if (timed) profile_end(t, st);
-
-        ApplyArgs aa{};
-        aa.X = ta.X; aa.C = ta.C; aa.d4 = ta.d4; aa.delta = reinterpret_cast<float4*>(w.delta);
-        aa.positions = cur.mask + 1; aa.slots = ps.slots; aa.shared = ps.shared;
-        const unsigned resolve_blocks = prep_blocks(next.refs);
-        const unsigned sweep_blocks = aa.positions / kSweepPerBlock;
-        const unsigned apply_grid = resolve_blocks + sweep_blocks;
-        hipLaunchKernelGGL(apply_kernel, dim3(apply_grid), dim3(256), 0, st, aa, next, resolve_blocks,
-                           resolve_blocks ? apply_grid / resolve_blocks : 1u);
-        e = hipGetLastError();
-        if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("apply launch: ") + hipGetErrorString(e));
-        t->batches_done += 1;
-        cur = next;
-    }
-    return NE_OK;
+    return run_batches(t, n_batches, R, 0, K, lr_host, st, prep_args,
+                       [&](const TrainArgs& ta, const PrepArgs& next) { return launch_train(shape, ta, next, st); });
 }
 
 ne_status ne_train_block(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t n_pairs, int64_t B,
@@ -1690,41 +1702,9 @@ ne_status ne_train_walks(ne_tables* t, const ne_alias* al, const int32_t* walks_
         return pa;
     };
 
-    PrepArgs cur = prep_args(0);
-    const unsigned grid0 = prep_blocks(cur.refs);
-    hipLaunchKernelGGL(claim_kernel, dim3(grid0), dim3(256), 0, st, cur);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("claim launch: ") + hipGetErrorString(e));
-    hipLaunchKernelGGL(resolve_kernel, dim3(grid0), dim3(256), 0, st, cur);
-    e = hipGetLastError();
-    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("resolve launch: ") + hipGetErrorString(e));
-
-    for (int64_t i = 0; i < n_batches; ++i) {
-        const PrepArgs next = prep_args(i + 1);
-        const PrepSlot& ps = w.prep[i & 1];
-        TrainArgs ta{};
-        ta.X = reinterpret_cast<float4*>(t->vertex); ta.C = reinterpret_cast<float4*>(t->context);
-        ta.B = cur.refs / R; ta.window = window; ta.K = K; ta.d4 = t->dim / 4; ta.lr = lr_host[i];
-        ta.ids = ps.ids; ta.posbuf = ps.posbuf; ta.shared = ps.shared; ta.delta = w.delta;
-        const bool timed = profile_begin(t, st);
-        e = by_segments ? launch_train_seg(shape, ta, next, static_cast<unsigned>(ta.B), st) : launch_train_walk(shape, ta, next, st);
-        if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("train launch: ") + hipGetErrorString(e));
-        if (timed) profile_end(t, st);
-
-        ApplyArgs aa{};
-        aa.X = ta.X; aa.C = ta.C; aa.d4 = ta.d4; aa.delta = reinterpret_cast<float4*>(w.delta);
-        aa.positions = cur.mask + 1; aa.slots = ps.slots; aa.shared = ps.shared;
-        const unsigned resolve_blocks = prep_blocks(next.refs);
-        const unsigned sweep_blocks = aa.positions / kSweepPerBlock;
-        const unsigned apply_grid = resolve_blocks + sweep_blocks;
-        hipLaunchKernelGGL(apply_kernel, dim3(apply_grid), dim3(256), 0, st, aa, next, resolve_blocks,
-                           resolve_blocks ? apply_grid / resolve_blocks : 1u);
-        e = hipGetLastError();
-        if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("apply launch: ") + hipGetErrorString(e));
-        t->batches_done += 1;
-        cur = next;
-    }
-    return NE_OK;
+    return run_batches(t, n_batches, R, window, K, lr_host, st, prep_args, [&](const TrainArgs& ta, const PrepArgs& next) {
+        return by_segments ? launch_train_seg(shape, ta, next, static_cast<unsigned>(ta.B), st) : launch_train_walk(shape, ta, next, st);
+    });
 }
 
 ne_status ne_train_batch(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t B, int32_t K,
