@@ -151,3 +151,35 @@ def train(train_edges: np.ndarray, num_nodes: int, dim: int = 64, epochs: int = 
         done += n
     torch.cuda.synchronize(dev)
     return tables, alias
+
+
+def main(argv=None) -> int:
+    """python -m paper_2005_13789_amd.linkpred EDGES.txt [options]: split, train, report the AUC."""
+    import argparse
+    import json
+    ap = argparse.ArgumentParser(description="Link-prediction AUC of SGNS embeddings trained on an edge list (Sec. V-B protocol)")
+    ap.add_argument("edges", help='text file with one "u v" edge per line (# and % start comments)')
+    ap.add_argument("--test-fraction", type=float, default=0.01, help="share of the edges held out (the paper: 1 %% on YouTube)")
+    ap.add_argument("--dim", type=int, default=128)
+    ap.add_argument("--epochs", type=int, default=10)
+    ap.add_argument("--negatives", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=65536)
+    ap.add_argument("--lr", type=float, default=0.025)
+    ap.add_argument("--walk-length", type=int, default=40)
+    ap.add_argument("--window", type=int, default=5)
+    ap.add_argument("--mode", default="sync", choices=["sync", "walks", "async"])
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args(argv)
+    edges, n = read_edge_list(args.edges)
+    train_edges, test_edges = split_edges(edges, args.test_fraction, args.seed)
+    tables, _alias = train(train_edges, n, dim=args.dim, epochs=args.epochs, negatives=args.negatives, batch=args.batch,
+                           lr0=args.lr, walk_length=args.walk_length, window=args.window, seed=args.seed, mode=args.mode)
+    all_edges = np.concatenate([train_edges, test_edges])
+    print(json.dumps({"nodes": n, "train_edges": int(train_edges.shape[0]), "test_edges": int(test_edges.shape[0]),
+                      "auc_vertex_context": evaluate(tables, n, all_edges, test_edges, args.seed + 1, True),
+                      "auc_vertex_vertex": evaluate(tables, n, all_edges, test_edges, args.seed + 1, False)}))
+    return 0
+
+
+if __name__ == "__main__":
+    raise SystemExit(main())

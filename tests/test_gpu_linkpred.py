@@ -75,3 +75,14 @@ def test_link_prediction_auc_on_planted_partition(mode, batch):
     assert abs(auc0 - 0.5) < 0.05
     # one edge in eleven of this network is random and cannot be predicted: the ceiling is about 0.955
     assert auc_vc > 0.9 and auc_vv > 0.9
+
+
+def test_command_line_on_an_edge_list_file(tmp_path, capsys):
+    import json
+    edges = planted_partition(1000, communities=10, inside=8, outside=1, seed=5)
+    f = tmp_path / "edges.txt"
+    f.write_text("# u v\n" + "\n".join(f"{a + 100} {b + 100}" for a, b in edges.tolist()) + "\n")    # ids need not start at 0
+    assert lp.main([str(f), "--test-fraction", "0.1", "--dim", "32", "--epochs", "8", "--batch", "2048", "--mode", "walks"]) == 0
+    out = json.loads(capsys.readouterr().out.strip().splitlines()[-1])
+    print(out, flush=True)
+    assert out["nodes"] == 1000 and out["auc_vertex_context"] > 0.85
