@@ -45,7 +45,8 @@ WORKLOADS = {
     "c1": dict(V=10_000, edges=100_000, d=128, K=5, B=4096, grid=1, abc=(0.57, 0.19, 0.19), walk=(40, 5), seed=0),
     "c2": dict(V=1_000_000, edges=20_000_000, d=128, K=5, B=65536, grid=1, abc=(0.57, 0.19, 0.19), walk=(80, 5), seed=1),
     "c3": dict(V=100_000_000, edges=2_000_000_000, d=128, K=5, B=65536, grid=4, abc=(0.57, 0.19, 0.19), walk=None, seed=2),
-    "c4": dict(V=20_000_000, edges=400_000_000, d=512, K=10, B=32768, grid=1, abc=(0.57, 0.19, 0.19), walk=None, seed=3),
+    "c4": dict(V=20_000_000, edges=400_000_000, d=512, K=10, B=32768, grid=1, abc=(0.57, 0.19, 0.19), walk=None, seed=3,
+               walk_shape=(80, 10)),
     "c5": dict(V=50_000_000, edges=1_000_000_000, d=256, K=0, B=8192, grid=1, abc=(0.65, 0.15, 0.15), walk=None, seed=4,
                shared_negatives=1024),
 }
@@ -263,7 +264,7 @@ def walks_scenario(args, dev):
         print("bench.py: --walks does not apply to the shared-negative workload", file=sys.stderr)
         sys.exit(2)
     V, d, K, B, seed = w["V"], w["d"], w["K"], w["B"], w["seed"]
-    L, win = w["walk"] if w["walk"] is not None else (80, 5)
+    L, win = w["walk"] if w["walk"] is not None else w.get("walk_shape", (80, 5))
     per_walk = sum(L - j for j in range(1, win + 1))
     wpb = max(1, B // per_walk)                       # walks per batch: as many whole walks as fit into B samples
     n_batches = args.steps + args.warmup
