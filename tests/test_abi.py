@@ -77,6 +77,42 @@ def test_host_side_argument_errors():
     assert b"zero" in L.ne_last_error()
     assert L.ne_build_neg_alias(ctypes.byref(out), deg, 0, 0, fake, None) == ne.NE_ERR_ARG
     assert L.ne_build_neg_alias(ctypes.byref(out), deg, 4, -1, fake, None) == ne.NE_ERR_ARG
+    # walks: (tables, alias, walks, n_walks, walks_per_batch, walk_len, window, K, lr, sample_base, neg_out, stream)
+    def walks(tb=tables, al=None, w=fake, n=4, wpb=2, length=10, window=3, K=0, lrs=lr):
+        return L.ne_train_walks(tb, al, w, n, wpb, length, window, K, lrs, 0, None, None)
+
+    assert walks(tb=None) == ne.NE_ERR_ARG
+    assert walks(K=63) == ne.NE_ERR_ARG
+    assert walks(K=5) == ne.NE_ERR_ARG                  # K > 0, no alias
+    assert walks(length=1) == ne.NE_ERR_ARG
+    assert walks(length=65537) == ne.NE_ERR_ARG
+    assert walks(window=0) == ne.NE_ERR_ARG
+    assert walks(window=65) == ne.NE_ERR_ARG
+    assert b"window" in L.ne_last_error()
+    assert walks(n=-1) == ne.NE_ERR_ARG
+    assert walks(n=0, w=None) == ne.NE_OK               # nothing to do
+    assert walks(w=None) == ne.NE_ERR_ARG
+    assert walks(w=ctypes.c_void_p(0x1002)) == ne.NE_ERR_ARG
+    assert walks(wpb=0) == ne.NE_ERR_ARG
+    assert walks(lrs=None) == ne.NE_ERR_ARG
+    assert walks(lrs=(ctypes.c_float * 2)(0.1, float("inf"))) == ne.NE_ERR_ARG
+    assert walks() == ne.NE_ERR_STATE                   # no workspace
+    # pinned pairs: (tables, alias, pairs_host, n_pairs, B, K, lr, sample_base, staging, neg_out, stream); a NULL
+    # host pointer is refused before any HIP call is made
+    assert L.ne_train_block_pinned(tables, None, None, 10, 8, 0, lr, 0, fake, None, None) == ne.NE_ERR_ARG
+    assert b"pairs_host_pinned" in L.ne_last_error()
+    assert L.ne_train_block_pinned(None, None, None, 0, 8, 0, lr, 0, fake, None, None) == ne.NE_ERR_ARG
+    assert L.ne_train_block_pinned(tables, None, None, 0, 8, 0, lr, 0, None, None, None) == ne.NE_ERR_ARG   # as ne_train_block: pairs NULL
+    # scores: (tables, pairs, n, second_from_context, scores, stream)
+    assert L.ne_score_pairs(None, fake, 1, 1, fake, None) == ne.NE_ERR_ARG
+    assert L.ne_score_pairs(tables, fake, -1, 1, fake, None) == ne.NE_ERR_ARG
+    assert L.ne_score_pairs(tables, None, 1, 1, fake, None) == ne.NE_ERR_ARG
+    assert L.ne_score_pairs(tables, ctypes.c_void_p(0x1004), 1, 1, fake, None) == ne.NE_ERR_ARG
+    assert L.ne_score_pairs(tables, fake, 1, 1, None, None) == ne.NE_ERR_ARG
+    assert L.ne_score_pairs(tables, None, 0, 1, None, None) == ne.NE_OK
+    assert L.ne_validate_pairs(tables, fake, 1, None, None) == ne.NE_ERR_ARG
+    assert L.ne_validate_pairs(tables, fake, -1, fake, None) == ne.NE_ERR_ARG
+    assert L.ne_validate_pairs(tables, None, 0, fake, None) == ne.NE_OK
     L.ne_destroy_tables(tables)
 
 
