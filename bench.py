@@ -87,6 +87,12 @@ def build_workload(name: str, n_batches: int, dev):
     return w, degree, bp, sched
 
 
+def apply_tuning(args, tables):
+    if args.tuning:
+        list_cap, sweep = (int(v) for v in args.tuning.split(","))
+        ne.ne_set_tuning(tables, list_cap, sweep)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -108,6 +114,8 @@ def main():
     ap.add_argument("--walks", action="store_true",
                     help="on-device augmentation scenario (walk workloads c1, c2): the same whole-walk batches through "
                          "ne_train_walks and, expanded to pairs, through ne_train_block")
+    ap.add_argument("--tuning", default="", metavar="LIST_CAP,SWEEP",
+                    help="override the library's automatic choices (ne_set_tuning), e.g. 0,8 or 8,2 (experiments)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run 20 plain 1 GiB device copies (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -151,6 +159,7 @@ def main():
     else:
         workspace = torch.empty(ne.ne_workspace_bytes(d, B, K), dtype=torch.uint8, device=dev)
         tables = ne.ne_create_tables(vertex, context, seed, init=True, max_batch=B, max_negatives=K, workspace=workspace)
+        apply_tuning(args, tables)
     # one alias table per context block (a GPU's context partition is fixed; negatives come from it)
     block = bp.block_rows
     deg_host = degree.to(torch.int64).clamp_(max=2**32 - 1).cpu().numpy().astype(np.uint32)
@@ -301,6 +310,7 @@ def walks_scenario(args, dev):
         context = torch.empty((V, d), dtype=torch.float32, device=dev)
         ws = torch.empty(ne.ne_workspace_bytes(d, max_B, K), dtype=torch.uint8, device=dev)
         tables = ne.ne_create_tables(vertex, context, seed, init=True, max_batch=max_B, max_negatives=K, workspace=ws)
+        apply_tuning(args, tables)
         at = torch.empty((V, 2), dtype=torch.int32, device=dev)
         alias = ne.ne_build_neg_alias(degree.clamp(max=2**32 - 1).cpu().numpy().astype(np.uint32), 0, at)
         lrs = [np.float32(wl.linear_decay_lr(0.025, i * Bp, n_batches * Bp)) for i in range(n_batches)]

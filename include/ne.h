@@ -244,6 +244,21 @@ ne_status ne_score_pairs(const ne_tables* tables, const int32_t* pairs_dev, int6
                          int32_t second_from_context, float* scores_dev, void* hip_stream);
 
 /*
+ * Tuning of the exact step (ne_train_batch, ne_train_block, ne_train_block_pinned, ne_train_walks); the
+ * results are the same sums either way.  The paper fixes neither choice (it never describes its kernel).
+ *   list_cap          how a row that several references of a batch name ("shared row", Sec. III-B's
+ *                     conflict case inside one GPU) collects their deltas: its first list_cap
+ *                     references (0..8) store them with plain stores, one buffer row per reference,
+ *                     and the rest add to the row's accumulator with atomics.  0 = atomics only.
+ *                     -1 = automatic: 8 when the tables are small next to the batch
+ *                     (num_nodes <= 16 * rows named per batch), else 0.
+ *   sweep_per_thread  hash positions each thread of the apply kernel sweeps: 2, 4 or 8; 0 = automatic
+ *                     (2 with the list path, else 4).
+ * Takes effect from the next training call on this handle.  Errors: NE_ERR_ARG.
+ */
+ne_status ne_set_tuning(ne_tables* tables, int32_t list_cap, int32_t sweep_per_thread);
+
+/*
  * Debug helper for the sample format of Table I: counts ids in pairs_dev int32[B][2] that fall
  * outside [0, num_nodes) and adds the count to *bad_count_dev (device uint64, caller-zeroed).
  */

@@ -27,7 +27,7 @@ NE_MAX_BATCH = 1 << 22
 EXPORTS = (
     "ne_create_tables", "ne_build_neg_alias", "ne_workspace_bytes", "ne_train_batch", "ne_train_block", "ne_train_block_pinned", "ne_train_walks",
     "ne_shared_workspace_bytes", "ne_train_batch_shared", "ne_train_batch_async", "ne_set_vertex_window", "ne_eval_loss",
-    "ne_score_pairs", "ne_validate_pairs", "ne_profile_enable", "ne_profile_read", "ne_destroy_tables", "ne_destroy_alias", "ne_last_error",
+    "ne_score_pairs", "ne_set_tuning", "ne_validate_pairs", "ne_profile_enable", "ne_profile_read", "ne_destroy_tables", "ne_destroy_alias", "ne_last_error",
 )
 
 _lib = None
@@ -80,6 +80,8 @@ def lib() -> ctypes.CDLL:
     L.ne_train_walks.restype = c.c_int
     L.ne_score_pairs.argtypes = [vp, vp, c.c_int64, c.c_int32, vp, vp]
     L.ne_score_pairs.restype = c.c_int
+    L.ne_set_tuning.argtypes = [vp, c.c_int32, c.c_int32]
+    L.ne_set_tuning.restype = c.c_int
     L.ne_validate_pairs.argtypes = [vp, vp, c.c_int64, vp, vp]
     L.ne_validate_pairs.restype = c.c_int
     L.ne_profile_enable.argtypes = [vp, c.c_int32, c.c_int32]
@@ -318,6 +320,12 @@ def ne_score_pairs(tables: Tables, pairs: torch.Tensor, scores: torch.Tensor, se
         raise ValueError("scores is shorter than pairs")
     _check(lib().ne_score_pairs(tables.handle, pp, int(pairs.shape[0]), 1 if second_from_context else 0, sp,
                                 _stream_ptr(stream)))
+
+
+def ne_set_tuning(tables: Tables, list_cap: int = -1, sweep_per_thread: int = 0) -> None:
+    """How the exact step collects the deltas of rows that several references name (list_cap: -1 automatic,
+    0 atomics only, up to 8 listed references per row) and how finely the apply kernel sweeps (0 automatic, 2, 4, 8)."""
+    _check(lib().ne_set_tuning(tables.handle, list_cap, sweep_per_thread))
 
 
 def ne_validate_pairs(tables: Tables, pairs: torch.Tensor, bad_count: torch.Tensor, stream=None) -> None:

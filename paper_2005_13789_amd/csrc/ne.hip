@@ -16,9 +16,12 @@
 //          pair names is rewritten in place from registers (old + delta, one plain store: the row
 //          costs one read and one write).  A shared row is left untouched - other pairs must still
 //          read its pre-batch value - and its delta is added to the row's slot (indexed by hash
-//          position) with fp32 atomics.
-//   apply  adds each shared row's slot to the table row and zeroes the slot; the hash positions of
-//          the batch are emptied.
+//          position) with fp32 atomics.  Where most rows are shared the atomics' rate would bound
+//          the kernel; there the first references to arrive at a row (ranked by a returning
+//          counter, which is cheap) instead store their delta with plain stores in a buffer row
+//          of their own and enter the row's member list.
+//   apply  adds each shared row's slot, and the buffer rows of its member list, to the table row,
+//          zeroes the slot and the counter; the hash positions of the batch are emptied.
 //
 // This is exactly minibatch-synchronous: no row that a second reference could read is written
 // before the apply phase, and all contributions to a row are summed.  fp32 atomics on gfx950
@@ -436,7 +439,29 @@ struct TrainArgs {
     const uint32_t* posbuf;
     const uint8_t* shared;
     float* delta;
+    // shared rows, list path: the first list_cap references to arrive at a row (0 = path off)
+    uint32_t list_cap;
+    uint32_t* count;      // [positions] references of the row that have arrived (zero between batches)
+    uint32_t* members;    // [positions][kListCap] reference indices of the first arrivals
+    float4* dbuf;         // [references][d4] their deltas
 };
+
+// Longest member list of a shared row.
+constexpr uint32_t kListCap = 8;
+
+// Rank of a reference among those arriving at its shared row (~0 with the list path off).  The
+// returning atomic is cheap next to a row's traffic and is issued early, so its latency hides
+// behind the row gathers.
+template <int G>
+__device__ __forceinline__ uint32_t arrival_rank(const TrainArgs& a, uint32_t pos, int lg)
+{
+    uint32_t r = ~0u;
+    if (a.list_cap) {
+        if (lg == 0) r = atomicAdd(&a.count[pos], 1u);
+        r = __shfl(r, 0, G);
+    }
+    return r;
+}
 
 // Element e = lg + m*G of a row, for m < 4*NCH: the layout in which one atomic instruction of a lane
 // group covers consecutive dwords.  The float4-chunk layout is turned into it through LDS.
@@ -451,6 +476,34 @@ __device__ __forceinline__ void to_consecutive(const float4 (&v)[NCH], float (&o
     __builtin_amdgcn_wave_barrier();
 }
 
+// Delta dv of reference `ref` to the shared row at hash position pos.  A reference that arrived among
+// the first list_cap stores it with plain stores in its own row of dbuf and enters the row's member
+// list (the apply kernel sums the list); a later one adds it to the row's slot with atomics, which
+// retire one dword per memory channel clock and would otherwise bound batches with many shared rows.
+template <int G, int NCH>
+__device__ __forceinline__ void shared_row_delta(const TrainArgs& a, uint32_t pos, uint32_t ref, uint32_t rank,
+                                                 const float4 (&dv)[NCH], float* lds_row, int lg, int d4)
+{
+    if (rank < a.list_cap) {
+        float4* out = a.dbuf + static_cast<int64_t>(ref) * d4;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const int ci = lg + i * G;
+            if (ci < d4) out[ci] = dv[i];
+        }
+        if (lg == 0) a.members[static_cast<int64_t>(pos) * kListCap + rank] = ref;
+    } else {
+        float t[4 * NCH];
+        to_consecutive<G, NCH>(dv, t, lds_row, lg);
+        float* slot = a.delta + static_cast<int64_t>(pos) * (d4 * 4);
+#pragma unroll
+        for (int m = 0; m < 4 * NCH; ++m) {
+            const int e = lg + m * G;
+            if (e < d4 * 4) unsafeAtomicAdd(slot + e, t[m]);
+        }
+    }
+}
+
 // K+1 context rows of one pair (rows 0..K; with POS_FIRST row 0 is the positive, every other row a
 // negative), JB at a time: gather, score against x, form g_j, add g_j c_j to dx, and update the row:
 // rewritten in place if only this reference names it, else its delta goes to the row's slot with
@@ -458,8 +511,11 @@ __device__ __forceinline__ void to_consecutive(const float4 (&v)[NCH], float (&o
 template <int G, int NCH, int JB, int LANE0, bool POS_FIRST = true>
 __device__ __forceinline__ void context_rows_of_pair(const TrainArgs& a, int K, int d4, int d, const float4 (&xr)[NCH],
                                                      const float (&xt)[4 * NCH], float4 (&dx)[NCH], int32_t id_mine,
-                                                     uint32_t pos_mine, int shared_mine, int lg)
+                                                     uint32_t pos_mine, int shared_mine, uint32_t ref_mine, int lg)
 {
+    // ranks of this pair's references to shared rows, all in one returning atomic
+    uint32_t rank_mine = ~0u;
+    if (a.list_cap && shared_mine) rank_mine = atomicAdd(&a.count[pos_mine], 1u);
     for (int j0 = 0; j0 <= K; j0 += JB) {
         float4 cr[JB][NCH];
         float part[JB];
@@ -492,6 +548,8 @@ __device__ __forceinline__ void context_rows_of_pair(const TrainArgs& a, int K, 
                 const float g = a.lr * ((POS_FIRST && j == 0) ? 1.0f - sg : -sg);
                 const int shared = __shfl(shared_mine, j + LANE0, G);
                 const uint32_t pos = __shfl(pos_mine, j + LANE0, G);
+                const uint32_t rank = __shfl(rank_mine, j + LANE0, G);
+                const uint32_t ref = __shfl(ref_mine, j + LANE0, G);
 #pragma unroll
                 for (int i = 0; i < NCH; ++i) dx[i] = axpy4(g, cr[jj][i], dx[i]);
                 if (!shared) {
@@ -500,6 +558,14 @@ __device__ __forceinline__ void context_rows_of_pair(const TrainArgs& a, int K, 
                         const int ci = lg + i * G;
                         if (ci < d4) crow[jj][ci] = axpy4(g, xr[i], cr[jj][i]);
                     }
+                } else if (rank < a.list_cap) {
+                    float4* out = a.dbuf + static_cast<int64_t>(ref) * d4;
+#pragma unroll
+                    for (int i = 0; i < NCH; ++i) {
+                        const int ci = lg + i * G;
+                        if (ci < d4) out[ci] = make_float4(g * xr[i].x, g * xr[i].y, g * xr[i].z, g * xr[i].w);
+                    }
+                    if (lg == 0) a.members[static_cast<int64_t>(pos) * kListCap + rank] = ref;
                 } else {
                     float* slot = a.delta + static_cast<int64_t>(pos) * d;
 #pragma unroll
@@ -549,11 +615,15 @@ __global__ __launch_bounds__(kTrainThreads) void train_kernel(TrainArgs a, PrepA
     int32_t id_mine = 0;
     uint32_t pos_mine = 0;
     int shared_mine = 0;
+    const uint32_t ref_mine = static_cast<uint32_t>(b * R + lg);
     if (lg < R) {
-        id_mine = a.ids[b * R + lg];
-        pos_mine = a.posbuf[b * R + lg];
+        id_mine = a.ids[ref_mine];
+        pos_mine = a.posbuf[ref_mine];
         shared_mine = a.shared[pos_mine];
     }
+    const int shared0 = __shfl(shared_mine, 0, G);
+    const uint32_t pos0 = __shfl(pos_mine, 0, G);
+    const uint32_t rank0 = shared0 ? arrival_rank<G>(a, pos0, lg) : ~0u;
 
     const int32_t src = __shfl(id_mine, 0, G);
     float4* xrow = a.X + static_cast<int64_t>(src) * d4;
@@ -570,10 +640,9 @@ __global__ __launch_bounds__(kTrainThreads) void train_kernel(TrainArgs a, PrepA
 #pragma unroll
     for (int i = 0; i < NCH; ++i) dx[i] = make_float4(0.f, 0.f, 0.f, 0.f);
 
-    context_rows_of_pair<G, NCH, JB, 1>(a, K, d4, d, xr, xt, dx, id_mine, pos_mine, shared_mine, lg);
+    // (lane 0's reference, the vertex row, has been ranked above)
+    context_rows_of_pair<G, NCH, JB, 1>(a, K, d4, d, xr, xt, dx, id_mine, pos_mine, lg >= 1 ? shared_mine : 0, ref_mine, lg);
 
-    const int shared0 = __shfl(shared_mine, 0, G);
-    const uint32_t pos0 = __shfl(pos_mine, 0, G);
     if (!shared0) {
 #pragma unroll
         for (int i = 0; i < NCH; ++i) {
@@ -582,14 +651,7 @@ __global__ __launch_bounds__(kTrainThreads) void train_kernel(TrainArgs a, PrepA
                 xrow[ci] = make_float4(xr[i].x + dx[i].x, xr[i].y + dx[i].y, xr[i].z + dx[i].z, xr[i].w + dx[i].w);
         }
     } else {
-        float dxt[4 * NCH];
-        to_consecutive<G, NCH>(dx, dxt, lds[grp], lg);
-        float* slot = a.delta + static_cast<int64_t>(pos0) * d;
-#pragma unroll
-        for (int m = 0; m < 4 * NCH; ++m) {
-            const int e = lg + m * G;
-            if (e < d) unsafeAtomicAdd(slot + e, dxt[m]);
-        }
+        shared_row_delta<G, NCH>(a, pos0, static_cast<uint32_t>(b * R), rank0, dx, lds[grp], lg, d4);
     }
 }
 
@@ -628,6 +690,7 @@ __global__ __launch_bounds__(kTrainThreads) void train_walk_kernel(TrainArgs a, 
     if (src < 0) return;    // no pair starts at this position (uniform over the group)
     const uint32_t pos0 = a.posbuf[ref0];
     const int shared0 = a.shared[pos0];
+    const uint32_t rank0 = shared0 ? arrival_rank<G>(a, pos0, lg) : ~0u;
 
     float4* xrow = a.X + static_cast<int64_t>(src) * d4;
     float4 xr[NCH];
@@ -648,8 +711,8 @@ __global__ __launch_bounds__(kTrainThreads) void train_walk_kernel(TrainArgs a, 
         int32_t id_mine = -1;
         uint32_t pos_mine = 0;
         int shared_mine = 0;
+        const int64_t ref = ref0 + 1 + static_cast<int64_t>(j) * (K + 1) + lg;
         if (lg <= K) {
-            const int64_t ref = ref0 + 1 + static_cast<int64_t>(j) * (K + 1) + lg;
             id_mine = a.ids[ref];
             if (id_mine >= 0) {
                 pos_mine = a.posbuf[ref];
@@ -657,7 +720,7 @@ __global__ __launch_bounds__(kTrainThreads) void train_walk_kernel(TrainArgs a, 
             }
         }
         if (__shfl(id_mine, 0, G) < 0) continue;   // the walk has no pair j here; a pair's references exist together
-        context_rows_of_pair<G, NCH, JB, 0>(a, K, d4, d, xr, xt, dx, id_mine, pos_mine, shared_mine, lg);
+        context_rows_of_pair<G, NCH, JB, 0>(a, K, d4, d, xr, xt, dx, id_mine, pos_mine, shared_mine, static_cast<uint32_t>(ref), lg);
     }
 
     if (!shared0) {
@@ -668,14 +731,7 @@ __global__ __launch_bounds__(kTrainThreads) void train_walk_kernel(TrainArgs a, 
                 xrow[ci] = make_float4(xr[i].x + dx[i].x, xr[i].y + dx[i].y, xr[i].z + dx[i].z, xr[i].w + dx[i].w);
         }
     } else {
-        float dxt[4 * NCH];
-        to_consecutive<G, NCH>(dx, dxt, lds[grp], lg);
-        float* slot = a.delta + static_cast<int64_t>(pos0) * d;
-#pragma unroll
-        for (int m = 0; m < 4 * NCH; ++m) {
-            const int e = lg + m * G;
-            if (e < d) unsafeAtomicAdd(slot + e, dxt[m]);
-        }
+        shared_row_delta<G, NCH>(a, pos0, static_cast<uint32_t>(ref0), rank0, dx, lds[grp], lg, d4);
     }
 }
 
@@ -729,7 +785,7 @@ __global__ __launch_bounds__(kTrainThreads) void train_seg_kernel(TrainArgs a, P
 
     // my entry's vertex row, and the context rows grp and grp + E of the segment's list
     const int32_t src = a.ids[ref0 + grp];
-    uint32_t pos_x = 0;
+    uint32_t pos_x = 0, rank_x = ~0u;
     int shared_x = 0;
     float4 xr[NCH];
 #pragma unroll
@@ -738,6 +794,7 @@ __global__ __launch_bounds__(kTrainThreads) void train_seg_kernel(TrainArgs a, P
     if (src >= 0) {
         pos_x = a.posbuf[ref0 + grp];
         shared_x = a.shared[pos_x];
+        if (shared_x) rank_x = arrival_rank<G>(a, pos_x, lg);
         xrow = a.X + static_cast<int64_t>(src) * d4;
 #pragma unroll
         for (int i = 0; i < NCH; ++i) {
@@ -787,13 +844,14 @@ __global__ __launch_bounds__(kTrainThreads) void train_seg_kernel(TrainArgs a, P
                 int32_t id_mine = -1;
                 uint32_t pos_mine = 0;
                 int shared_mine = 0;
+                const int64_t ref = ref0 + E + CT + (static_cast<int64_t>(grp) * W + (j - 1)) * K + lg;
                 if (lg < K) {
-                    const int64_t ref = ref0 + E + CT + (static_cast<int64_t>(grp) * W + (j - 1)) * K + lg;
                     id_mine = a.ids[ref];
                     pos_mine = a.posbuf[ref];
                     shared_mine = a.shared[pos_mine];
                 }
-                context_rows_of_pair<G, NCH, JB, 0, false>(a, K - 1, d4, d, xr, xt, dx, id_mine, pos_mine, shared_mine, lg);
+                context_rows_of_pair<G, NCH, JB, 0, false>(a, K - 1, d4, d, xr, xt, dx, id_mine, pos_mine, shared_mine,
+                                                           static_cast<uint32_t>(ref), lg);
             }
         }
         if (!shared_x) {
@@ -804,14 +862,7 @@ __global__ __launch_bounds__(kTrainThreads) void train_seg_kernel(TrainArgs a, P
                     xrow[ci] = make_float4(xr[i].x + dx[i].x, xr[i].y + dx[i].y, xr[i].z + dx[i].z, xr[i].w + dx[i].w);
             }
         } else {
-            float dxt[4 * NCH];
-            to_consecutive<G, NCH>(dx, dxt, scratch + grp * ROW, lg);
-            float* slot = a.delta + static_cast<int64_t>(pos_x) * d;
-#pragma unroll
-            for (int m = 0; m < 4 * NCH; ++m) {
-                const int e = lg + m * G;
-                if (e < d) unsafeAtomicAdd(slot + e, dxt[m]);
-            }
+            shared_row_delta<G, NCH>(a, pos_x, static_cast<uint32_t>(ref0 + grp), rank_x, dx, scratch + grp * ROW, lg, d4);
         }
     }
 
@@ -820,6 +871,10 @@ __global__ __launch_bounds__(kTrainThreads) void train_seg_kernel(TrainArgs a, P
     for (int row = grp; row < CT; row += E) {
         const int32_t id = cid[row];
         if (id < 0) continue;
+        const int64_t ref = ref0 + E + row;
+        const uint32_t pos_c = a.posbuf[ref];
+        const int shared_c = a.shared[pos_c];
+        const uint32_t rank_c = shared_c ? arrival_rank<G>(a, pos_c, lg) : ~0u;
         float4 cr[NCH], dc[NCH];
 #pragma unroll
         for (int i = 0; i < NCH; ++i) {
@@ -841,9 +896,7 @@ __global__ __launch_bounds__(kTrainThreads) void train_seg_kernel(TrainArgs a, P
 #pragma unroll
             for (int i = 0; i < NCH; ++i) dc[i] = axpy4(g0, xv[i], dc[i]);
         }
-        const int64_t ref = ref0 + E + row;
-        const uint32_t pos_c = a.posbuf[ref];
-        if (!a.shared[pos_c]) {
+        if (!shared_c) {
             float4* crow = a.C + static_cast<int64_t>(id) * d4;
 #pragma unroll
             for (int i = 0; i < NCH; ++i) {
@@ -852,14 +905,7 @@ __global__ __launch_bounds__(kTrainThreads) void train_seg_kernel(TrainArgs a, P
                     crow[ci] = make_float4(cr[i].x + dc[i].x, cr[i].y + dc[i].y, cr[i].z + dc[i].z, cr[i].w + dc[i].w);
             }
         } else {
-            float dct[4 * NCH];
-            to_consecutive<G, NCH>(dc, dct, scratch + grp * ROW, lg);
-            float* slot = a.delta + static_cast<int64_t>(pos_c) * d;
-#pragma unroll
-            for (int m = 0; m < 4 * NCH; ++m) {
-                const int e = lg + m * G;
-                if (e < d) unsafeAtomicAdd(slot + e, dct[m]);
-            }
+            shared_row_delta<G, NCH>(a, pos_c, static_cast<uint32_t>(ref), rank_c, dc, scratch + grp * ROW, lg, d4);
         }
     }
 }
@@ -871,11 +917,15 @@ __global__ __launch_bounds__(kTrainThreads) void train_seg_kernel(TrainArgs a, P
 //   the rest              sweep the batch's hash positions in order, 8 per thread: read the shared
 //                         flags, empty the positions and clear the flags with full-width stores
 //                         (a linear pass is far cheaper than one partial store per reference), collect
-//                         the shared rows in LDS, then 16-lane groups add each row's slot to the
-//                         table row and zero the slot.
+//                         the shared rows in LDS, then 16-lane groups add each row's deltas - the
+//                         buffer rows of its member list, the slot if references beyond the list
+//                         used it - to the table row and zero what they used.
 // ---------------------------------------------------------------------------------------------
-constexpr int kSweepPerThread = 8;
-constexpr int kSweepPerBlock = 256 * kSweepPerThread;
+// Positions per sweep thread are a launch choice (2, 4 or 8): fewer give the row work more workgroups,
+// more make the sweep itself cheaper.  Position counts are multiples of the largest block's span.
+constexpr int kSweepPerBlock = 256 * 8;
+
+__device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
 
 struct ApplyArgs {
     float4* X;
@@ -885,12 +935,18 @@ struct ApplyArgs {
     uint32_t positions;   // hash positions in use for this batch (a power of two, multiple of 2048)
     unsigned long long* slots;
     uint8_t* shared;
+    uint32_t list_cap;    // as in TrainArgs
+    uint32_t* count;
+    const uint32_t* members;
+    const float4* dbuf;
 };
 
+template <int kSweepPerThread>
 __global__ __launch_bounds__(256) void apply_kernel(ApplyArgs a, PrepArgs next, unsigned resolve_blocks,
                                                     unsigned period)
 {
-    __shared__ uint2 todo_list[kSweepPerBlock];   // (position, key) of the shared rows of this block's span
+    constexpr int kSpan = 256 * kSweepPerThread;   // positions per workgroup
+    __shared__ uint2 todo_list[kSpan];   // (position, key) of the shared rows of this block's span
     __shared__ int todo_count;
     unsigned block;
     if (fused_block(resolve_blocks, period, &block)) {
@@ -899,10 +955,12 @@ __global__ __launch_bounds__(256) void apply_kernel(ApplyArgs a, PrepArgs next, 
     }
     if (threadIdx.x == 0) todo_count = 0;
     __syncthreads();
-    const uint32_t first = block * kSweepPerBlock + threadIdx.x * kSweepPerThread;
-    const uint64_t flags = *reinterpret_cast<const uint64_t*>(a.shared + first);
+    const uint32_t first = block * kSpan + threadIdx.x * kSweepPerThread;
+    using flags_t = std::conditional_t<kSweepPerThread == 8, uint64_t, std::conditional_t<kSweepPerThread == 4, uint32_t, uint16_t>>;
+    static_assert(kSweepPerThread == 8 || kSweepPerThread == 4 || kSweepPerThread == 2, "flags are read as one word");
+    const uint64_t flags = *reinterpret_cast<const flags_t*>(a.shared + first);
     if (flags) {
-        *reinterpret_cast<uint64_t*>(a.shared + first) = 0ull;
+        *reinterpret_cast<flags_t*>(a.shared + first) = 0;
 #pragma unroll
         for (int i = 0; i < kSweepPerThread; ++i) {
             if ((flags >> (8 * i)) & 0xFFull) {
@@ -924,19 +982,45 @@ __global__ __launch_bounds__(256) void apply_kernel(ApplyArgs a, PrepArgs next, 
         const uint2 item = todo_list[e];
         float4* row = ((item.y & 0x80000000u) ? a.C : a.X) + static_cast<int64_t>(item.y & 0x7FFFFFFFu) * a.d4;
         float4* slot = a.delta + static_cast<int64_t>(item.x) * a.d4;
+        // list path: the row's first arrivals left their deltas in dbuf; only later ones used the slot
+        uint32_t listed = 0, member = 0;
+        bool use_slot = true;
+        if (a.list_cap) {
+            const uint32_t arrived = a.count[item.x];
+            // (entries past the list's end hold stale indices; they are not used)
+            if (static_cast<uint32_t>(lg) < kListCap) member = a.members[static_cast<int64_t>(item.x) * kListCap + lg];
+            listed = arrived < a.list_cap ? arrived : a.list_cap;
+            use_slot = arrived > listed;
+            if (lg == 0) a.count[item.x] = 0u;
+        }
         for (int c0 = 0; c0 < a.d4; c0 += 32) {
             const int ca = c0 + lg, cb = c0 + 16 + lg;
             const bool va = ca < a.d4, vb = cb < a.d4;
-            float4 sa, sb, ra, rb;
-            if (va) { sa = slot[ca]; ra = row[ca]; }
-            if (vb) { sb = slot[cb]; rb = row[cb]; }
-            if (va) {
-                row[ca] = make_float4(ra.x + sa.x, ra.y + sa.y, ra.z + sa.z, ra.w + sa.w);
-                slot[ca] = make_float4(0.f, 0.f, 0.f, 0.f);
+            float4 ra = make_float4(0.f, 0.f, 0.f, 0.f), rb = ra;
+            if (va) ra = row[ca];
+            if (vb) rb = row[cb];
+            if (use_slot) {
+                if (va) ra = add4(ra, slot[ca]);
+                if (vb) rb = add4(rb, slot[cb]);
             }
-            if (vb) {
-                row[cb] = make_float4(rb.x + sb.x, rb.y + sb.y, rb.z + sb.z, rb.w + sb.w);
-                slot[cb] = make_float4(0.f, 0.f, 0.f, 0.f);
+            float4 da[kListCap], db[kListCap];
+#pragma unroll
+            for (uint32_t r = 0; r < kListCap; ++r) {   // all of the list's loads in flight together
+                const float4* dv = a.dbuf + static_cast<int64_t>(__shfl(member, static_cast<int>(r), 16)) * a.d4;
+                da[r] = db[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (r < listed && va) da[r] = dv[ca];
+                if (r < listed && vb) db[r] = dv[cb];
+            }
+#pragma unroll
+            for (uint32_t r = 0; r < kListCap; ++r) {
+                ra = add4(ra, da[r]);
+                rb = add4(rb, db[r]);
+            }
+            if (va) row[ca] = ra;
+            if (vb) row[cb] = rb;
+            if (use_slot) {
+                if (va) slot[ca] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (vb) slot[cb] = make_float4(0.f, 0.f, 0.f, 0.f);
             }
         }
     }
@@ -1264,6 +1348,23 @@ constexpr uint32_t kHashFactorMax = 4;
 constexpr unsigned kFetchBlocks = 8;
 inline uint32_t hash_factor(int64_t num_nodes, uint32_t refs) { return num_nodes <= 16 * static_cast<int64_t>(refs) ? 2u : 4u; }
 
+// How a batch treats its shared rows.  Tables that are small next to the batch (the condition that also
+// halves the hash) make most references name shared rows: the train kernel is then bound by the
+// atomics' rate, and the list path (plain stores per reference, summed by the apply kernel) measured
+// +20 % (1 M nodes, 458 752 references); elsewhere the atomics hide behind the row traffic and the
+// list path costs 4-6 %.  The sweep gives each thread 4 positions (2 with the list path, whose row
+// work is longer): 8 made the sweep cheaper but left the row work too few workgroups (-3.6 %).
+// ne_set_tuning overrides both.
+struct BatchTuning { uint32_t list_cap; int sweep_per_thread; };
+inline BatchTuning batch_tuning(const ne_tables* t, uint32_t refs)
+{
+    const bool small_tables = hash_factor(t->num_nodes, refs) == 2;
+    BatchTuning b;
+    b.list_cap = t->tune_list_cap >= 0 ? static_cast<uint32_t>(t->tune_list_cap) : (small_tables ? kListCap : 0u);
+    b.sweep_per_thread = t->tune_sweep > 0 ? t->tune_sweep : (small_tables ? 2 : 4);
+    return b;
+}
+
 bool workspace_layout(int32_t dim, int64_t max_B, int32_t max_K, char* base, Workspace* w)
 {
     if (dim < 4 || dim > NE_MAX_DIM || dim % 4 != 0 || max_B < 1 || max_B > kMaxBatch || max_K < 0 ||
@@ -1283,6 +1384,9 @@ bool workspace_layout(int32_t dim, int64_t max_B, int32_t max_K, char* base, Wor
         w->prep[i].posbuf = reinterpret_cast<uint32_t*>(take(refs * 4));
     }
     w->delta = reinterpret_cast<float*>(take(cap * static_cast<size_t>(dim) * 4));
+    w->count = reinterpret_cast<uint32_t*>(take(cap * 4));
+    w->members = reinterpret_cast<uint32_t*>(take(cap * static_cast<size_t>(kListCap) * 4));
+    w->dbuf = reinterpret_cast<float*>(take(refs * static_cast<size_t>(dim) * 4));
     w->total_bytes = off;
     return true;
 }
@@ -1337,6 +1441,8 @@ ne_status run_batches(ne_tables* t, int64_t n_batches, int64_t R, int32_t window
         ta.X = reinterpret_cast<float4*>(t->vertex); ta.C = reinterpret_cast<float4*>(t->context);
         ta.B = cur.refs / R; ta.window = window; ta.K = K; ta.d4 = t->dim / 4; ta.lr = lr_host[i];
         ta.ids = ps.ids; ta.posbuf = ps.posbuf; ta.shared = ps.shared; ta.delta = w.delta;
+        const BatchTuning tune = batch_tuning(t, cur.refs);
+        ta.list_cap = tune.list_cap; ta.count = w.count; ta.members = w.members; ta.dbuf = reinterpret_cast<float4*>(w.dbuf);
         const bool timed = profile_begin(t, st);
         e = train(ta, next);
         if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("train launch: ") + hipGetErrorString(e));
@@ -1345,11 +1451,15 @@ ne_status run_batches(ne_tables* t, int64_t n_batches, int64_t R, int32_t window
         ApplyArgs aa{};
         aa.X = ta.X; aa.C = ta.C; aa.d4 = ta.d4; aa.delta = reinterpret_cast<float4*>(w.delta);
         aa.positions = cur.mask + 1; aa.slots = ps.slots; aa.shared = ps.shared;
+        aa.list_cap = ta.list_cap; aa.count = w.count; aa.members = w.members; aa.dbuf = ta.dbuf;
         const unsigned resolve_blocks = prep_blocks(next.refs);
-        const unsigned sweep_blocks = aa.positions / kSweepPerBlock;
+        const int per_thread = tune.sweep_per_thread;
+        const unsigned sweep_blocks = aa.positions / (256u * per_thread);
         const unsigned apply_grid = resolve_blocks + sweep_blocks;
-        hipLaunchKernelGGL(apply_kernel, dim3(apply_grid), dim3(256), 0, st, aa, next, resolve_blocks,
-                           resolve_blocks ? apply_grid / resolve_blocks : 1u);
+        const unsigned period = resolve_blocks ? apply_grid / resolve_blocks : 1u;
+        if (per_thread == 2) hipLaunchKernelGGL(apply_kernel<2>, dim3(apply_grid), dim3(256), 0, st, aa, next, resolve_blocks, period);
+        else if (per_thread == 4) hipLaunchKernelGGL(apply_kernel<4>, dim3(apply_grid), dim3(256), 0, st, aa, next, resolve_blocks, period);
+        else hipLaunchKernelGGL(apply_kernel<8>, dim3(apply_grid), dim3(256), 0, st, aa, next, resolve_blocks, period);
         e = hipGetLastError();
         if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("apply launch: ") + hipGetErrorString(e));
         t->batches_done += 1;
@@ -1392,6 +1502,7 @@ ne_status ne_create_tables(ne_tables** out, int64_t num_nodes, int32_t dim, floa
     if (!t) return fail(NE_ERR_NOMEM, "host allocation failed");
     t->num_nodes = num_nodes; t->dim = dim; t->vertex = vertex_dev; t->context = context_dev; t->seed = seed;
     t->max_batch = 0; t->max_negatives = 0; t->batches_done = 0; t->profile_every = 0; t->ev_used = 0;
+    t->tune_list_cap = -1; t->tune_sweep = 0;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
 
     if (workspace_dev || max_batch > 0) {   // training requested
@@ -1411,6 +1522,7 @@ ne_status ne_create_tables(ne_tables** out, int64_t num_nodes, int32_t dim, floa
             if (e == hipSuccess) e = launch_fill(reinterpret_cast<uint32_t*>(w.prep[i].shared), w.cap / 4, 0u, st);
         }
         if (e == hipSuccess) e = launch_fill(reinterpret_cast<uint32_t*>(w.delta), static_cast<size_t>(w.cap) * dim, 0u, st);
+        if (e == hipSuccess) e = launch_fill(w.count, w.cap, 0u, st);
         if (e != hipSuccess) {
             delete t;
             return fail(NE_ERR_HIP, std::string("workspace init launch: ") + hipGetErrorString(e));
@@ -1789,6 +1901,17 @@ ne_status ne_score_pairs(const ne_tables* t, const int32_t* pairs_dev, int64_t n
                        reinterpret_cast<const int2*>(pairs_dev), n, t->dim / 4, scores_dev);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("score launch: ") + hipGetErrorString(e));
+    return NE_OK;
+}
+
+ne_status ne_set_tuning(ne_tables* t, int32_t list_cap, int32_t sweep_per_thread)
+{
+    if (!t) return fail(NE_ERR_ARG, "tables handle is NULL");
+    if (list_cap < -1 || list_cap > static_cast<int32_t>(kListCap)) return fail(NE_ERR_ARG, "list_cap must be -1 (automatic) or in [0, 8]");
+    if (sweep_per_thread != 0 && sweep_per_thread != 2 && sweep_per_thread != 4 && sweep_per_thread != 8)
+        return fail(NE_ERR_ARG, "sweep_per_thread must be 0 (automatic), 2, 4 or 8");
+    t->tune_list_cap = list_cap;
+    t->tune_sweep = sweep_per_thread;
     return NE_OK;
 }
 

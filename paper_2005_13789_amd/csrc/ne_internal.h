@@ -39,6 +39,9 @@ struct PrepSlot {
 struct Workspace {
     PrepSlot prep[2];
     float* delta;        // [cap][dim]  per-position fp32 accumulators, zero between batches
+    uint32_t* count;     // [cap]       arrivals at a shared row's position, zero between batches
+    uint32_t* members;   // [cap][8]    reference indices of a shared row's first arrivals
+    float* dbuf;         // [max_B * (max_K + 2)][dim]  per-reference deltas of those arrivals
     uint32_t cap;        // power of two >= 4 * max_B * (max_K + 2)
     size_t total_bytes;
 };
@@ -55,6 +58,8 @@ struct ne_tables {
     int32_t max_negatives;
     Workspace ws;
     uint64_t batches_done;
+    int32_t tune_list_cap;   // ne_set_tuning: -1 = automatic
+    int32_t tune_sweep;      // ne_set_tuning: 0 = automatic
     // optional timing of the train kernel with HIP events (ne_profile_enable / ne_profile_read)
     int32_t profile_every;
     std::vector<hipEvent_t> ev_zero, ev_start, ev_stop;   // zero -> start brackets nothing: the events' own cost

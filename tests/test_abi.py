@@ -110,6 +110,13 @@ def test_host_side_argument_errors():
     assert L.ne_score_pairs(tables, ctypes.c_void_p(0x1004), 1, 1, fake, None) == ne.NE_ERR_ARG
     assert L.ne_score_pairs(tables, fake, 1, 1, None, None) == ne.NE_ERR_ARG
     assert L.ne_score_pairs(tables, None, 0, 1, None, None) == ne.NE_OK
+    assert L.ne_set_tuning(None, -1, 0) == ne.NE_ERR_ARG
+    assert L.ne_set_tuning(tables, -2, 0) == ne.NE_ERR_ARG
+    assert L.ne_set_tuning(tables, 9, 0) == ne.NE_ERR_ARG
+    assert L.ne_set_tuning(tables, 0, 3) == ne.NE_ERR_ARG
+    assert b"sweep_per_thread" in L.ne_last_error()
+    assert L.ne_set_tuning(tables, 8, 2) == ne.NE_OK
+    assert L.ne_set_tuning(tables, -1, 0) == ne.NE_OK
     assert L.ne_validate_pairs(tables, fake, 1, None, None) == ne.NE_ERR_ARG
     assert L.ne_validate_pairs(tables, fake, -1, fake, None) == ne.NE_ERR_ARG
     assert L.ne_validate_pairs(tables, None, 0, fake, None) == ne.NE_OK

@@ -89,7 +89,7 @@ def build_graph(V: int, edges: torch.Tensor) -> Graph:
     src = torch.cat([e[:, 0], e[:, 1]])
     dst = torch.cat([e[:, 1], e[:, 0]])
     order = torch.argsort(src, stable=True)
-    src, dst = src[order], dst[order]
+    src, dst = _take_rows(src, order), _take_rows(dst, order)
     degree = torch.bincount(src, minlength=V)
     indptr = torch.zeros(V + 1, dtype=torch.int64, device=edges.device)
     indptr[1:] = torch.cumsum(degree, 0)
@@ -110,6 +110,18 @@ def rmat_degrees(V: int, n_edges: int, seed: int, abc=(0.57, 0.19, 0.19), device
         done += n
         part += 1
     return deg
+
+
+def _take_rows(t: torch.Tensor, index: torch.Tensor, chunk: int = 1 << 24) -> torch.Tensor:
+    """t[index] for a 1-D index of any length, gathered a bounded number of rows at a time (one indexing
+    call over 2^26 rows of a two-column tensor fails to launch on this PyTorch build and leaves its output
+    unwritten)."""
+    if index.numel() <= chunk:
+        return t[index]
+    out = torch.empty((index.numel(),) + tuple(t.shape[1:]), dtype=t.dtype, device=t.device)
+    for lo in range(0, index.numel(), chunk):
+        out[lo:lo + chunk] = t[index[lo:lo + chunk]]
+    return out
 
 
 def random_walks(graph: Graph, starts: torch.Tensor, length: int, seed: int) -> torch.Tensor:
@@ -155,7 +167,7 @@ def walk_pairs(graph: Graph, length: int, window: int, n_pairs: int | None, seed
         parts.append(torch.stack([walks[:, :-j].reshape(-1), walks[:, j:].reshape(-1)], dim=1))
     pairs = torch.cat(parts)
     perm = torch.randperm(pairs.shape[0], generator=g, device=dev)
-    pairs = pairs[perm]
+    pairs = _take_rows(pairs, perm)
     if n_pairs is not None:
         pairs = pairs[:n_pairs]
     return pairs.to(torch.int32).contiguous()
@@ -202,7 +214,7 @@ def bucket_pairs(pairs: torch.Tensor, V: int, grid: int) -> BucketedPairs:
     counts = torch.bincount(bid, minlength=grid * grid).cpu()
     offsets = torch.zeros(grid * grid + 1, dtype=torch.int64)
     offsets[1:] = torch.cumsum(counts, 0)
-    return BucketedPairs(pairs[order].contiguous(), offsets, grid, block_rows)
+    return BucketedPairs(_take_rows(pairs, order).contiguous(), offsets, grid, block_rows)
 
 
 def orthogonal_schedule(bp: BucketedPairs, batch: int):
