@@ -62,3 +62,14 @@ def test_degrees_streamed_equals_graph_degrees_in_distribution():
     assert d1.shape == (V,) and int(d1.sum()) <= 80000 and int(d1.sum()) > 70000
     assert wl.linear_decay_lr(0.025, 0, 100) == 0.025
     assert wl.linear_decay_lr(0.025, 100, 100) == 0.025 * 1e-4
+
+
+def test_take_rows_in_chunks_equals_plain_indexing():
+    """Large gathers go through _take_rows a bounded number of rows at a time; any chunk size gives t[index]."""
+    g = torch.Generator().manual_seed(3)
+    t = torch.randint(0, 1000, (5000, 2), generator=g)
+    index = torch.randperm(5000, generator=g)
+    for chunk in (1, 7, 4999, 5000, 1 << 24):
+        assert torch.equal(wl._take_rows(t, index, chunk), t[index])
+    v = torch.arange(100)
+    assert torch.equal(wl._take_rows(v, torch.tensor([5, 1, 99]), 2), torch.tensor([5, 1, 99]))
