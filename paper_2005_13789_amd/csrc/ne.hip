@@ -941,7 +941,7 @@ struct ApplyArgs {
     const float4* dbuf;
 };
 
-template <int kSweepPerThread>
+template <int kSweepPerThread, int CH>
 __global__ __launch_bounds__(256) void apply_kernel(ApplyArgs a, PrepArgs next, unsigned resolve_blocks,
                                                     unsigned period)
 {
@@ -993,34 +993,47 @@ __global__ __launch_bounds__(256) void apply_kernel(ApplyArgs a, PrepArgs next, 
             use_slot = arrived > listed;
             if (lg == 0) a.count[item.x] = 0u;
         }
-        for (int c0 = 0; c0 < a.d4; c0 += 32) {
-            const int ca = c0 + lg, cb = c0 + 16 + lg;
-            const bool va = ca < a.d4, vb = cb < a.d4;
-            float4 ra = make_float4(0.f, 0.f, 0.f, 0.f), rb = ra;
-            if (va) ra = row[ca];
-            if (vb) rb = row[cb];
-            if (use_slot) {
-                if (va) ra = add4(ra, slot[ca]);
-                if (vb) rb = add4(rb, slot[cb]);
-            }
-            float4 da[kListCap], db[kListCap];
+        // CH chunks of a row per lane and pass, all of a pass's loads issued before its stores (a
+        // 2 KB row in passes of 2 chunks would pay four dependent round trips instead of one)
+        for (int c0 = 0; c0 < a.d4; c0 += 16 * CH) {
+            float4 acc[CH];
+            bool valid[CH];
 #pragma unroll
-            for (uint32_t r = 0; r < kListCap; ++r) {   // all of the list's loads in flight together
-                const float4* dv = a.dbuf + static_cast<int64_t>(__shfl(member, static_cast<int>(r), 16)) * a.d4;
-                da[r] = db[r] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (r < listed && va) da[r] = dv[ca];
-                if (r < listed && vb) db[r] = dv[cb];
+            for (int i = 0; i < CH; ++i) {
+                const int ci = c0 + lg + 16 * i;
+                valid[i] = ci < a.d4;
+                acc[i] = valid[i] ? row[ci] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+            if (use_slot) {
+                float4 sv[CH];
+#pragma unroll
+                for (int i = 0; i < CH; ++i) sv[i] = valid[i] ? slot[c0 + lg + 16 * i] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                for (int i = 0; i < CH; ++i) acc[i] = add4(acc[i], sv[i]);
+            }
+            // the list's buffer rows, MB members' loads in flight together
+            constexpr uint32_t MB = 16 / CH < kListCap ? 16 / CH : kListCap;
+            for (uint32_t r0 = 0; r0 < listed; r0 += MB) {
+                float4 dv[MB][CH];
+#pragma unroll
+                for (uint32_t r = 0; r < MB; ++r) {
+                    const float4* src = a.dbuf + static_cast<int64_t>(__shfl(member, static_cast<int>((r0 + r) & (kListCap - 1)), 16)) * a.d4;
+#pragma unroll
+                    for (int i = 0; i < CH; ++i)
+                        dv[r][i] = (r0 + r < listed && valid[i]) ? src[c0 + lg + 16 * i] : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+                for (uint32_t r = 0; r < MB; ++r)
+#pragma unroll
+                    for (int i = 0; i < CH; ++i) acc[i] = add4(acc[i], dv[r][i]);
             }
 #pragma unroll
-            for (uint32_t r = 0; r < kListCap; ++r) {
-                ra = add4(ra, da[r]);
-                rb = add4(rb, db[r]);
-            }
-            if (va) row[ca] = ra;
-            if (vb) row[cb] = rb;
+            for (int i = 0; i < CH; ++i)
+                if (valid[i]) row[c0 + lg + 16 * i] = acc[i];
             if (use_slot) {
-                if (va) slot[ca] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (vb) slot[cb] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                for (int i = 0; i < CH; ++i)
+                    if (valid[i]) slot[c0 + lg + 16 * i] = make_float4(0.f, 0.f, 0.f, 0.f);
             }
         }
     }
@@ -1457,9 +1470,12 @@ ne_status run_batches(ne_tables* t, int64_t n_batches, int64_t R, int32_t window
         const unsigned sweep_blocks = aa.positions / (256u * per_thread);
         const unsigned apply_grid = resolve_blocks + sweep_blocks;
         const unsigned period = resolve_blocks ? apply_grid / resolve_blocks : 1u;
-        if (per_thread == 2) hipLaunchKernelGGL(apply_kernel<2>, dim3(apply_grid), dim3(256), 0, st, aa, next, resolve_blocks, period);
-        else if (per_thread == 4) hipLaunchKernelGGL(apply_kernel<4>, dim3(apply_grid), dim3(256), 0, st, aa, next, resolve_blocks, period);
-        else hipLaunchKernelGGL(apply_kernel<8>, dim3(apply_grid), dim3(256), 0, st, aa, next, resolve_blocks, period);
+        const bool wide = aa.d4 > 32;   // rows of more than 2 chunks per lane: passes of 8 (measured +1 % at dim 512; -1 to -7 % at dim 128)
+#define NE_APPLY(S_, C_) hipLaunchKernelGGL((apply_kernel<S_, C_>), dim3(apply_grid), dim3(256), 0, st, aa, next, resolve_blocks, period)
+        if (per_thread == 2) { if (wide) NE_APPLY(2, 8); else NE_APPLY(2, 2); }
+        else if (per_thread == 4) { if (wide) NE_APPLY(4, 8); else NE_APPLY(4, 2); }
+        else { if (wide) NE_APPLY(8, 8); else NE_APPLY(8, 2); }
+#undef NE_APPLY
         e = hipGetLastError();
         if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("apply launch: ") + hipGetErrorString(e));
         t->batches_done += 1;
