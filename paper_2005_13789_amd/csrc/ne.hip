@@ -506,8 +506,9 @@ __device__ __forceinline__ void shared_row_delta(const TrainArgs& a, uint32_t po
 
 // K+1 context rows of one pair (rows 0..K; with POS_FIRST row 0 is the positive, every other row a
 // negative), JB at a time: gather, score against x, form g_j, add g_j c_j to dx, and update the row:
-// rewritten in place if only this reference names it, else its delta goes to the row's slot with
-// atomics.  Lane j + LANE0 of the group holds reference j's id, hash position and shared flag.
+// rewritten in place if only this reference names it, else its delta goes to the reference's buffer
+// row (list path, first arrivals) or to the row's slot with atomics.  Lane j + LANE0 of the group holds
+// reference j's id, hash position, shared flag and index in the batch.
 template <int G, int NCH, int JB, int LANE0, bool POS_FIRST = true>
 __device__ __forceinline__ void context_rows_of_pair(const TrainArgs& a, int K, int d4, int d, const float4 (&xr)[NCH],
                                                      const float (&xt)[4 * NCH], float4 (&dx)[NCH], int32_t id_mine,
