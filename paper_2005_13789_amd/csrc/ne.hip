@@ -1352,18 +1352,16 @@ hipError_t launch_async(const Shape& s, const AsyncArgs& a, hipStream_t st)
 
 // Largest batch: keeps every grid and the hash capacity inside 32 bits.
 constexpr int64_t kMaxBatch = static_cast<int64_t>(1) << 22;
-// Hash positions per reference (before rounding up to a power of two).  The workspace holds 4 per
-// reference.  A batch uses all of them (load <= 1/4: little probing) unless the tables are small
-// next to the batch: then most references name shared rows, and halving the positions in use
-// (load <= 1/2) halves the sweep and the footprint of the delta slots, which measured more than
-// pays for the extra probing (1 M nodes, 458 752 references: +8 %; 100 M nodes: -3 %).
-constexpr uint32_t kHashFactorMax = 4;
+// Hash positions per reference, before rounding up to a power of two (load <= 1/2).  Four per
+// reference mean less probing but a longer sweep and twice the footprint of the delta slots, and
+// measured slower at every size tried (100 M nodes x dim 128: -1.6 %, 20 M x 512: -6 %, 1 M x 128: -7 %);
+// eight: -12 %.
+constexpr uint32_t kHashFactor = 2;
 // helper workgroups that prefetch the samples of a later batch from pinned host memory (512 KB per batch of 65536)
 constexpr unsigned kFetchBlocks = 8;
-inline uint32_t hash_factor(int64_t num_nodes, uint32_t refs) { return num_nodes <= 16 * static_cast<int64_t>(refs) ? 2u : 4u; }
 
-// How a batch treats its shared rows.  Tables that are small next to the batch (the condition that also
-// halves the hash) make most references name shared rows: the train kernel is then bound by the
+// How a batch treats its shared rows.  Tables that are small next to the batch (num_nodes <= 16 x rows
+// named per batch) make most references name shared rows: the train kernel is then bound by the
 // atomics' rate, and the list path (plain stores per reference, summed by the apply kernel) measured
 // +20 % (1 M nodes, 458 752 references); elsewhere the atomics hide behind the row traffic and the
 // list path costs 4-6 %.  The sweep gives each thread 4 positions (2 with the list path, whose row
@@ -1372,7 +1370,7 @@ inline uint32_t hash_factor(int64_t num_nodes, uint32_t refs) { return num_nodes
 struct BatchTuning { uint32_t list_cap; int sweep_per_thread; };
 inline BatchTuning batch_tuning(const ne_tables* t, uint32_t refs)
 {
-    const bool small_tables = hash_factor(t->num_nodes, refs) == 2;
+    const bool small_tables = t->num_nodes <= 16 * static_cast<int64_t>(refs);
     BatchTuning b;
     b.list_cap = t->tune_list_cap >= 0 ? static_cast<uint32_t>(t->tune_list_cap) : (small_tables ? kListCap : 0u);
     b.sweep_per_thread = t->tune_sweep > 0 ? t->tune_sweep : (small_tables ? 2 : 4);
@@ -1386,7 +1384,7 @@ bool workspace_layout(int32_t dim, int64_t max_B, int32_t max_K, char* base, Wor
         return false;
     const uint64_t refs = static_cast<uint64_t>(max_B) * (max_K + 2);
     uint64_t cap = 2048;   // one sweep block of the apply kernel
-    while (cap < kHashFactorMax * refs) cap <<= 1;
+    while (cap < kHashFactor * refs) cap <<= 1;
     auto up = [](size_t v) { return (v + 255) & ~static_cast<size_t>(255); };
     size_t off = 0;
     auto take = [&](size_t bytes) { char* p = base + off; off = up(off + bytes); return p; };
@@ -1719,8 +1717,8 @@ static ne_status train_block_impl(ne_tables* t, const ne_alias* al, const int32_
         pa.sample_base = sample_base + static_cast<uint64_t>(first);
         pa.k0 = static_cast<uint32_t>(t->seed); pa.k1 = static_cast<uint32_t>(t->seed >> 32);
         pa.alias = al ? al->table : nullptr; pa.alias_n = al ? static_cast<uint64_t>(al->n) : 1; pa.alias_base = al ? al->base : 0;
-        uint32_t positions = kSweepPerBlock;     // hash positions this batch uses: 2 or 4 per reference
-        while (positions < hash_factor(t->num_nodes, static_cast<uint32_t>(Bi * R)) * static_cast<uint32_t>(Bi * R)) positions <<= 1;
+        uint32_t positions = kSweepPerBlock;     // hash positions this batch uses
+        while (positions < kHashFactor * static_cast<uint32_t>(Bi * R)) positions <<= 1;
         pa.slots = ps.slots; pa.mask = positions - 1; pa.shared = ps.shared; pa.ids = ps.ids; pa.posbuf = ps.posbuf;
         pa.neg_out = neg_out_dev ? neg_out_dev + first * K : nullptr;
         return pa;
@@ -1824,8 +1822,8 @@ ne_status ne_train_walks(ne_tables* t, const ne_alias* al, const int32_t* walks_
         pa.sample_base = sample_base + static_cast<uint64_t>(first * per_walk);
         pa.k0 = static_cast<uint32_t>(t->seed); pa.k1 = static_cast<uint32_t>(t->seed >> 32);
         pa.alias = al ? al->table : nullptr; pa.alias_n = al ? static_cast<uint64_t>(al->n) : 1; pa.alias_base = al ? al->base : 0;
-        uint32_t positions = kSweepPerBlock;     // hash positions this batch uses: 2 or 4 per reference
-        while (positions < hash_factor(t->num_nodes, pa.refs) * pa.refs) positions <<= 1;
+        uint32_t positions = kSweepPerBlock;     // hash positions this batch uses
+        while (positions < kHashFactor * pa.refs) positions <<= 1;
         pa.slots = ps.slots; pa.mask = positions - 1; pa.shared = ps.shared; pa.ids = ps.ids; pa.posbuf = ps.posbuf;
         pa.neg_out = neg_out_dev ? neg_out_dev + first * per_walk * K : nullptr;
         return pa;

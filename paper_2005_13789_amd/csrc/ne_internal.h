@@ -42,7 +42,7 @@ struct Workspace {
     uint32_t* count;     // [cap]       arrivals at a shared row's position, zero between batches
     uint32_t* members;   // [cap][8]    reference indices of a shared row's first arrivals
     float* dbuf;         // [max_B * (max_K + 2)][dim]  per-reference deltas of those arrivals
-    uint32_t cap;        // power of two >= 4 * max_B * (max_K + 2)
+    uint32_t cap;        // power of two >= 2 * max_B * (max_K + 2)
     size_t total_bytes;
 };
 
