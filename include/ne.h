@@ -251,7 +251,7 @@ ne_status ne_score_pairs(const ne_tables* tables, const int32_t* pairs_dev, int6
  *                     references (0..8) store them with plain stores, one buffer row per reference,
  *                     and the rest add to the row's accumulator with atomics.  0 = atomics only.
  *                     -1 = automatic: 8 when the tables are small next to the batch
- *                     (num_nodes <= 16 * rows named per batch), else 0.
+ *                     (num_nodes <= min(20, 1500 / dim) * rows named per batch), else 0.
  *   sweep_per_thread  hash positions each thread of the apply kernel sweeps: 2, 4 or 8; 0 = automatic
  *                     (2 with the list path, else 4).
  * Takes effect from the next training call on this handle.  Errors: NE_ERR_ARG.

@@ -1360,17 +1360,19 @@ constexpr uint32_t kHashFactor = 2;
 // helper workgroups that prefetch the samples of a later batch from pinned host memory (512 KB per batch of 65536)
 constexpr unsigned kFetchBlocks = 8;
 
-// How a batch treats its shared rows.  Tables that are small next to the batch (num_nodes <= 16 x rows
-// named per batch) make most references name shared rows: the train kernel is then bound by the
-// atomics' rate, and the list path (plain stores per reference, summed by the apply kernel) measured
-// +20 % (1 M nodes, 458 752 references); elsewhere the atomics hide behind the row traffic and the
-// list path costs 4-6 %.  The sweep gives each thread 4 positions (2 with the list path, whose row
-// work is longer): 8 made the sweep cheaper but left the row work too few workgroups (-3.6 %).
+// How a batch treats its shared rows.  Tables that are small next to the batch make most references name
+// shared rows: the train kernel is then bound by the atomics' rate, and the list path (plain stores per
+// reference, summed by the apply kernel) pays: +20 % at 1 M nodes x dim 128 with 458 752 references per
+// batch.  Where the atomics hide behind the row traffic it costs 4-12 %.  Break-even, measured on R-MAT
+// pairs as nodes per reference: 20 at dim 32, 12 at dim 128, 8 at dim 256, 4 at dim 512 (K = 10); the
+// rule below stays a little under it.  The sweep gives each thread 4 positions (2 with the list path,
+// whose row work is longer): 8 made the sweep cheaper but left the row work too few workgroups (-3.6 %).
 // ne_set_tuning overrides both.
 struct BatchTuning { uint32_t list_cap; int sweep_per_thread; };
 inline BatchTuning batch_tuning(const ne_tables* t, uint32_t refs)
 {
-    const bool small_tables = t->num_nodes <= 16 * static_cast<int64_t>(refs);
+    const int64_t per_ref = 1500 / t->dim < 20 ? 1500 / t->dim : 20;   // nodes per reference up to which lists pay
+    const bool small_tables = t->num_nodes <= per_ref * static_cast<int64_t>(refs);
     BatchTuning b;
     b.list_cap = t->tune_list_cap >= 0 ? static_cast<uint32_t>(t->tune_list_cap) : (small_tables ? kListCap : 0u);
     b.sweep_per_thread = t->tune_sweep > 0 ? t->tune_sweep : (small_tables ? 2 : 4);
