@@ -107,3 +107,32 @@ def test_tuning_argument_errors():
         with pytest.raises(ne.NeError):
             ne.ne_set_tuning(t, *bad)
     ne.ne_set_tuning(t, -1, 0)
+
+
+@pytest.mark.parametrize("list_cap", [0, 1, 2, 7, 8])
+@pytest.mark.parametrize("d", [128, 512])
+def test_exact_multiplicities_around_the_list_capacity(list_cap, d):
+    """Row k (k = 1..12) is named exactly k times as a source and row 100 + k exactly k times as a context, no
+    negatives: lists shorter than, as long as and one short of the number of references, in one batch."""
+    say(f"multiplicities 1..12, d={d}, list_cap={list_cap}")
+    V, K = 400, 0
+    src, ctx = [], []
+    for k in range(1, 13):
+        for i in range(k):
+            src.append(k); ctx.append(200 + 13 * k + i)          # source row k, k times, with distinct contexts
+            src.append(300 + (7 * k + i) % 90); ctx.append(100 + k)   # context row 100 + k, k times
+    rng = np.random.default_rng(d + list_cap)
+    order = rng.permutation(len(src))
+    pairs = np.stack([np.array(src)[order], np.array(ctx)[order]], axis=1).astype(np.int32)
+    B = pairs.shape[0]
+    t = make(V, d, B, K, 3)
+    ne.ne_set_tuning(t, list_cap, 0)
+    Xo, Co = t.vertex.cpu().numpy(), t.context.cpu().numpy()
+    for rep in range(2):       # the second batch finds counters, lists and accumulators clean
+        ne.ne_train_batch(t, None, torch.from_numpy(pairs).to(DEV), K, 0.05, 0)
+        torch.cuda.synchronize()
+        oracle.train_batch(Xo, Co, pairs, np.zeros((B, 0), np.int32), 0.05)
+        ex = rowwise_rel_err(t.vertex.cpu().numpy(), Xo, floor_frac=1e-3)
+        ec = rowwise_rel_err(t.context.cpu().numpy(), Co, floor_frac=1e-3)
+        say(f"  batch {rep}: row error X {ex:.2e} C {ec:.2e}")
+        assert ex <= 1e-5 * (rep + 1) and ec <= 1e-5 * (rep + 1)
