@@ -942,7 +942,7 @@ struct ApplyArgs {
     const float4* dbuf;
 };
 
-template <int kSweepPerThread, int CH>
+template <int kSweepPerThread, int GL, int CH>
 __global__ __launch_bounds__(256) void apply_kernel(ApplyArgs a, PrepArgs next, unsigned resolve_blocks,
                                                     unsigned period)
 {
@@ -978,8 +978,8 @@ __global__ __launch_bounds__(256) void apply_kernel(ApplyArgs a, PrepArgs next, 
     }
     __syncthreads();
     const int n = todo_count;
-    const int lg = threadIdx.x & 15;
-    for (int e = threadIdx.x >> 4; e < n; e += 16) {
+    const int lg = threadIdx.x & (GL - 1);
+    for (int e = threadIdx.x / GL; e < n; e += 256 / GL) {
         const uint2 item = todo_list[e];
         float4* row = ((item.y & 0x80000000u) ? a.C : a.X) + static_cast<int64_t>(item.y & 0x7FFFFFFFu) * a.d4;
         float4* slot = a.delta + static_cast<int64_t>(item.x) * a.d4;
@@ -996,32 +996,32 @@ __global__ __launch_bounds__(256) void apply_kernel(ApplyArgs a, PrepArgs next, 
         }
         // CH chunks of a row per lane and pass, all of a pass's loads issued before its stores (a
         // 2 KB row in passes of 2 chunks would pay four dependent round trips instead of one)
-        for (int c0 = 0; c0 < a.d4; c0 += 16 * CH) {
+        for (int c0 = 0; c0 < a.d4; c0 += GL * CH) {
             float4 acc[CH];
             bool valid[CH];
 #pragma unroll
             for (int i = 0; i < CH; ++i) {
-                const int ci = c0 + lg + 16 * i;
+                const int ci = c0 + lg + GL * i;
                 valid[i] = ci < a.d4;
                 acc[i] = valid[i] ? row[ci] : make_float4(0.f, 0.f, 0.f, 0.f);
             }
             if (use_slot) {
                 float4 sv[CH];
 #pragma unroll
-                for (int i = 0; i < CH; ++i) sv[i] = valid[i] ? slot[c0 + lg + 16 * i] : make_float4(0.f, 0.f, 0.f, 0.f);
+                for (int i = 0; i < CH; ++i) sv[i] = valid[i] ? slot[c0 + lg + GL * i] : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
                 for (int i = 0; i < CH; ++i) acc[i] = add4(acc[i], sv[i]);
             }
             // the list's buffer rows, MB members' loads in flight together
-            constexpr uint32_t MB = 16 / CH < kListCap ? 16 / CH : kListCap;
+            constexpr uint32_t MB = CH >= 16 ? 1 : (16 / CH < kListCap ? 16 / CH : kListCap);
             for (uint32_t r0 = 0; r0 < listed; r0 += MB) {
                 float4 dv[MB][CH];
 #pragma unroll
                 for (uint32_t r = 0; r < MB; ++r) {
-                    const float4* src = a.dbuf + static_cast<int64_t>(__shfl(member, static_cast<int>((r0 + r) & (kListCap - 1)), 16)) * a.d4;
+                    const float4* src = a.dbuf + static_cast<int64_t>(__shfl(member, static_cast<int>((r0 + r) & (kListCap - 1)), GL)) * a.d4;
 #pragma unroll
                     for (int i = 0; i < CH; ++i)
-                        dv[r][i] = (r0 + r < listed && valid[i]) ? src[c0 + lg + 16 * i] : make_float4(0.f, 0.f, 0.f, 0.f);
+                        dv[r][i] = (r0 + r < listed && valid[i]) ? src[c0 + lg + GL * i] : make_float4(0.f, 0.f, 0.f, 0.f);
                 }
 #pragma unroll
                 for (uint32_t r = 0; r < MB; ++r)
@@ -1030,11 +1030,11 @@ __global__ __launch_bounds__(256) void apply_kernel(ApplyArgs a, PrepArgs next, 
             }
 #pragma unroll
             for (int i = 0; i < CH; ++i)
-                if (valid[i]) row[c0 + lg + 16 * i] = acc[i];
+                if (valid[i]) row[c0 + lg + GL * i] = acc[i];
             if (use_slot) {
 #pragma unroll
                 for (int i = 0; i < CH; ++i)
-                    if (valid[i]) slot[c0 + lg + 16 * i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (valid[i]) slot[c0 + lg + GL * i] = make_float4(0.f, 0.f, 0.f, 0.f);
             }
         }
     }
@@ -1471,11 +1471,21 @@ ne_status run_batches(ne_tables* t, int64_t n_batches, int64_t R, int32_t window
         const unsigned sweep_blocks = aa.positions / (256u * per_thread);
         const unsigned apply_grid = resolve_blocks + sweep_blocks;
         const unsigned period = resolve_blocks ? apply_grid / resolve_blocks : 1u;
-        const bool wide = aa.d4 > 32;   // rows of more than 2 chunks per lane: passes of 8 (measured +1 % at dim 512; -1 to -7 % at dim 128)
-#define NE_APPLY(S_, C_) hipLaunchKernelGGL((apply_kernel<S_, C_>), dim3(apply_grid), dim3(256), 0, st, aa, next, resolve_blocks, period)
-        if (per_thread == 2) { if (wide) NE_APPLY(2, 8); else NE_APPLY(2, 2); }
-        else if (per_thread == 4) { if (wide) NE_APPLY(4, 8); else NE_APPLY(4, 2); }
-        else { if (wide) NE_APPLY(8, 8); else NE_APPLY(8, 2); }
+        // Row work of the apply kernel: GL lanes per row, CH dwordx4 chunks per lane and pass.  One chunk per
+        // lane where a row has 32 or more (as in the train kernel; +1.1 % at dim 128), except with the list
+        // path, whose passes keep several buffer rows in flight (16 lanes measured +1.8 % there); rows of more
+        // than 2 chunks per lane go in passes of 8 (+1 % at dim 512).
+        const bool wide = aa.d4 > 32, lanes32 = aa.d4 >= 32 && aa.list_cap == 0;
+#define NE_APPLY(S_, G_, C_) hipLaunchKernelGGL((apply_kernel<S_, G_, C_>), dim3(apply_grid), dim3(256), 0, st, aa, next, resolve_blocks, period)
+#define NE_APPLY_SHAPE(S_)                                                                        \
+    do {                                                                                          \
+        if (lanes32) { if (wide) NE_APPLY(S_, 32, 8); else NE_APPLY(S_, 32, 1); }                 \
+        else { if (wide) NE_APPLY(S_, 16, 8); else NE_APPLY(S_, 16, 2); }                         \
+    } while (0)
+        if (per_thread == 2) NE_APPLY_SHAPE(2);
+        else if (per_thread == 4) NE_APPLY_SHAPE(4);
+        else NE_APPLY_SHAPE(8);
+#undef NE_APPLY_SHAPE
 #undef NE_APPLY
         e = hipGetLastError();
         if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("apply launch: ") + hipGetErrorString(e));
