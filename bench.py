@@ -38,7 +38,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per train-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see
 # profiles/), scaled by the factor a plain copy kernel of known size reads on the same counters.
 # None = not measured for that workload.
-TRAFFIC_BYTES_PER_LAUNCH = {"c1": None, "c2": None, "c3": 556.5e6, "c4": None, "c5": None}
+TRAFFIC_BYTES_PER_LAUNCH = {"c1": None, "c2": None, "c3": 554.7e6, "c4": None, "c5": None}
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 WORKLOADS = {
