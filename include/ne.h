@@ -196,6 +196,27 @@ ne_status ne_train_batch_shared(ne_tables* tables, const ne_alias* alias, const 
                                 double* loss_sum_dev, void* hip_stream);
 
 /*
+ * ne_train_batch_shared for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus
+ * the workspace), same kernels, same result.  The scratch is a static device array of
+ * NE_SHARED_STATIC_SCRATCH_BYTES (32 MiB) inside the library, one per GPU, held from the moment the
+ * library's code is loaded on that GPU until the process ends; its address is looked up on the first
+ * call on each device.  The call allocates and frees nothing.
+ *   Limit: ne_shared_workspace_bytes(dim, B, N) <= NE_SHARED_STATIC_SCRATCH_BYTES (for example dim 256
+ *   with B <= 2048 and N <= 512, or dim 128 with B <= 4096 and N <= 1024); larger shapes return
+ *   NE_ERR_ARG and a message that names both sizes.
+ *   All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two
+ *   host threads) race and give wrong results; order them on one stream.  Nothing in the array has to
+ *   survive from one call to the next, and nothing in it has to start at zero: every call rewrites what
+ *   it reads.
+ * Errors: as ne_train_batch_shared, and NE_ERR_HIP if the array's address cannot be obtained.
+ */
+enum { NE_SHARED_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024 };
+ne_status ne_train_batch_shared_static(ne_tables* tables, const ne_alias* alias, const int32_t* pairs_dev,
+                                       int64_t B, int32_t N, float lr, float neg_scale, uint64_t batch_index,
+                                       int32_t* neg_out_dev, double* loss_sum_dev, void* hip_stream);
+
+/*
  * Per-sample ("asynchronous") training: the same arithmetic as ne_train_batch, but every pair is
  * trained on its own as in the loop of Algorithm 1, without waiting for the other pairs of the
  * call: each pair reads its 2+K rows as they are at that moment and writes all of them back at once

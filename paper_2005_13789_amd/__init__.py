@@ -26,7 +26,7 @@ NE_MAX_BATCH = 1 << 22
 
 EXPORTS = (
     "ne_create_tables", "ne_build_neg_alias", "ne_workspace_bytes", "ne_train_batch", "ne_train_block", "ne_train_block_pinned", "ne_train_walks",
-    "ne_shared_workspace_bytes", "ne_train_batch_shared", "ne_train_batch_async", "ne_set_vertex_window", "ne_eval_loss",
+    "ne_shared_workspace_bytes", "ne_train_batch_shared", "ne_train_batch_shared_static", "ne_train_batch_async", "ne_set_vertex_window", "ne_eval_loss",
     "ne_score_pairs", "ne_set_tuning", "ne_validate_pairs", "ne_profile_enable", "ne_profile_read", "ne_destroy_tables", "ne_destroy_alias", "ne_last_error",
 )
 
@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
     L.ne_train_batch_shared.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_float, c.c_float, c.c_uint64, vp,
                                         c.c_size_t, vp, vp, vp]
     L.ne_train_batch_shared.restype = c.c_int
+    L.ne_train_batch_shared_static.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_float, c.c_float, c.c_uint64, vp, vp, vp]
+    L.ne_train_batch_shared_static.restype = c.c_int
     L.ne_train_batch_async.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_float, c.c_uint64, vp, vp]
     L.ne_train_batch_async.restype = c.c_int
     L.ne_set_vertex_window.argtypes = [vp, vp, c.c_int64, c.c_int64]
@@ -294,6 +296,24 @@ def ne_train_batch_shared(tables: Tables, alias: Alias, pairs: torch.Tensor, N: 
         raise TypeError("neg_out needs N int32 elements")
     _check(lib().ne_train_batch_shared(tables.handle, alias.handle if alias else None, pp, B, N, lr, neg_scale,
                                        batch_index, wp, workspace.numel(), np_, lp, _stream_ptr(stream)))
+
+
+NE_SHARED_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
+
+
+def ne_train_batch_shared_static(tables: Tables, alias: Alias, pairs: torch.Tensor, N: int, lr: float, neg_scale: float,
+                                 batch_index: int, neg_out: torch.Tensor | None = None,
+                                 loss_sum: torch.Tensor | None = None, stream=None) -> None:
+    """ne_train_batch_shared on the library's static per-GPU scratch (no workspace argument, nothing allocated);
+    shapes whose workspace exceeds NE_SHARED_STATIC_SCRATCH_BYTES are refused."""
+    B = int(pairs.shape[0])
+    pp = _dev_ptr(pairs, torch.int32, "pairs")
+    np_ = _dev_ptr(neg_out, torch.int32, "neg_out")
+    lp = _dev_ptr(loss_sum, torch.float64, "loss_sum")
+    if neg_out is not None and neg_out.numel() < N:
+        raise TypeError("neg_out needs N int32 elements")
+    _check(lib().ne_train_batch_shared_static(tables.handle, alias.handle if alias else None, pp, B, N, lr, neg_scale,
+                                              batch_index, np_, lp, _stream_ptr(stream)))
 
 
 def ne_eval_loss(tables: Tables, alias: Alias | None, pairs: torch.Tensor, K: int, sample_base: int,

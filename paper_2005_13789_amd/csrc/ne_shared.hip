@@ -24,8 +24,15 @@
 #include <hip/hip_bf16.h>
 
 #include <atomic>
+#include <mutex>
 
 #include "ne_internal.h"
+
+// Workspace of ne_train_batch_shared_static: one array per GPU, part of the loaded code object, so the
+// entry point has nothing to allocate.  The name below is only a host-side stand-in; the device
+// address comes from hipGetSymbolAddress (static_scratch_of_current_device) and is what the kernels get.
+constexpr size_t kStaticScratchBytes = static_cast<size_t>(NE_SHARED_STATIC_SCRATCH_BYTES);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -700,9 +707,10 @@ size_t ne_shared_workspace_bytes(int32_t dim, int64_t B, int32_t N)
     return w.total;
 }
 
-ne_status ne_train_batch_shared(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t B, int32_t N,
-                                float lr, float neg_scale, uint64_t batch_index, void* workspace_dev,
-                                size_t workspace_bytes, int32_t* neg_out_dev, double* loss_sum_dev, void* hip_stream)
+// Argument checks and launches common to both entry points; `what` names the workspace in messages.
+static ne_status train_shared_impl(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t B, int32_t N, float lr,
+                                   float neg_scale, uint64_t batch_index, void* workspace_dev, size_t workspace_bytes,
+                                   bool static_scratch, int32_t* neg_out_dev, double* loss_sum_dev, void* hip_stream)
 {
     if (!t || !al) return fail(NE_ERR_ARG, "tables or alias handle is NULL");
     if (B < 0) return fail(NE_ERR_ARG, "B is negative");
@@ -714,8 +722,14 @@ ne_status ne_train_batch_shared(ne_tables* t, const ne_alias* al, const int32_t*
     SharedWs w;
     if (!shared_layout(t->dim, B, N, static_cast<char*>(workspace_dev), &w))
         return fail(NE_ERR_ARG, "shared-negative mode needs dim in {64, 128, 256}, 1 <= B <= 2^20, N a multiple of 128 in [128, 65536]");
-    if (!workspace_dev || !aligned(workspace_dev, 256) || workspace_bytes < w.total)
+    if (static_scratch) {
+        if (w.total > workspace_bytes)
+            return fail(NE_ERR_ARG, "this (dim, B, N) needs " + std::to_string(w.total) + " bytes of scratch; the static scratch of "
+                                    "ne_train_batch_shared_static holds " + std::to_string(workspace_bytes) +
+                                    " (NE_SHARED_STATIC_SCRATCH_BYTES): use ne_train_batch_shared with a workspace of the caller");
+    } else if (!workspace_dev || !aligned(workspace_dev, 256) || workspace_bytes < w.total) {
         return fail(NE_ERR_ARG, "workspace_dev is NULL, not 256-byte aligned, or smaller than ne_shared_workspace_bytes()");
+    }
     if (loss_sum_dev && !aligned(loss_sum_dev, 8)) return fail(NE_ERR_ARG, "loss_sum_dev is misaligned");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     hipError_t e = hipErrorInvalidValue;
@@ -727,6 +741,46 @@ ne_status ne_train_batch_shared(ne_tables* t, const ne_alias* al, const int32_t*
     }
     if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("shared-negative launch: ") + hipGetErrorString(e));
     return NE_OK;
+}
+
+// Device address of `scratch` on the current device, looked up once per device (every GPU holds its
+// own copy of the array at its own address).
+static ne_status static_scratch_of_current_device(void** out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex lock;
+    static void* address[kMaxDevices] = {};
+    int device = -1;
+    NE_HIP_CHECK(hipGetDevice(&device));
+    if (device < 0 || device >= kMaxDevices) return fail(NE_ERR_STATE, "device index outside [0, 64)");
+    std::lock_guard<std::mutex> guard(lock);
+    if (!address[device]) {
+        void* p = nullptr;
+        NE_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || !aligned(p, 256)) return fail(NE_ERR_HIP, "hipGetSymbolAddress returned no usable address for the static scratch");
+        address[device] = p;
+    }
+    *out = address[device];
+    return NE_OK;
+}
+
+ne_status ne_train_batch_shared(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t B, int32_t N,
+                                float lr, float neg_scale, uint64_t batch_index, void* workspace_dev,
+                                size_t workspace_bytes, int32_t* neg_out_dev, double* loss_sum_dev, void* hip_stream)
+{
+    return train_shared_impl(t, al, pairs_dev, B, N, lr, neg_scale, batch_index, workspace_dev, workspace_bytes, false,
+                             neg_out_dev, loss_sum_dev, hip_stream);
+}
+
+ne_status ne_train_batch_shared_static(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t B, int32_t N,
+                                       float lr, float neg_scale, uint64_t batch_index, int32_t* neg_out_dev,
+                                       double* loss_sum_dev, void* hip_stream)
+{
+    void* ws = nullptr;
+    const ne_status rc = static_scratch_of_current_device(&ws);
+    if (rc != NE_OK) return rc;
+    return train_shared_impl(t, al, pairs_dev, B, N, lr, neg_scale, batch_index, ws, kStaticScratchBytes, true,
+                             neg_out_dev, loss_sum_dev, hip_stream);
 }
 
 }  // extern "C"
