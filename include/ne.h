@@ -10,7 +10,8 @@
  *
  * Update semantics are minibatch-synchronous: every gradient of a batch is evaluated at the tables
  * as they were before the batch, contributions to the same row are summed, and the sums are applied
- * once (the paper trains "in fully synchronous style", Sec. III-B).
+ * once (across GPUs the paper's training is synchronous as well, Sec. III-B; inside a GPU it fixes
+ * nothing).
  *
  * Conventions
  *  - "_dev" pointers are device memory owned by the caller; "_host" pointers are host memory.  The
@@ -101,6 +102,12 @@ ne_status ne_build_neg_alias(ne_alias** out, const uint32_t* degree_host, int64_
  *   s_j = <x, c_j>,  g_0 = 1 - sigmoid(s_0),  g_k = -sigmoid(s_k),
  *   vertex[src] += lr * sum_j g_j c_j,   context[id_j] += lr * g_j x,
  * contributions to the same row summed (in fp32; the order of the sum is not fixed).
+ * Accuracy: a row that one reference of the batch names is updated with one rounding per element.  A row
+ * that n references name has their n deltas added one after the other in fp32, so its update carries an
+ * accumulation error of up to about n * 2^-24 of the summed magnitudes: typically sqrt(n) * 2^-24, close
+ * to the bound when many of the contributions are identical (the same source row against the same context
+ * row many times).  Up to n of about 1700 that is inside a relative error of 1e-4 per row; a hub row that
+ * tens of thousands of samples of one batch name can exceed it (1.7e-4 measured at n = 4e5).
  * Calls on one handle must be ordered by the stream and must not overlap: the handle's workspace
  * carries state from one call to the next.  Errors: NE_ERR_ARG, NE_ERR_STATE, NE_ERR_HIP.
  */
@@ -267,8 +274,8 @@ ne_status ne_score_pairs(const ne_tables* tables, const int32_t* pairs_dev, int6
 /*
  * Tuning of the exact step (ne_train_batch, ne_train_block, ne_train_block_pinned, ne_train_walks); the
  * results are the same sums either way.  The paper fixes neither choice (it never describes its kernel).
- *   list_cap          how a row that several references of a batch name ("shared row", Sec. III-B's
- *                     conflict case inside one GPU) collects their deltas: its first list_cap
+ *   list_cap          how a row that several references of a batch name ("shared row") collects
+ *                     their deltas: its first list_cap
  *                     references (0..8) store them with plain stores, one buffer row per reference,
  *                     and the rest add to the row's accumulator with atomics.  0 = atomics only.
  *                     -1 = automatic: 8 when the tables are small next to the batch
@@ -285,6 +292,16 @@ ne_status ne_set_tuning(ne_tables* tables, int32_t list_cap, int32_t sweep_per_t
  */
 ne_status ne_validate_pairs(const ne_tables* tables, const int32_t* pairs_dev, int64_t B,
                             unsigned long long* bad_count_dev, void* hip_stream);
+
+/*
+ * Debug helper: the home position the exact step's duplicate detection gives a row key in a table of
+ * `positions` hash positions (a power of two in [2, 2^31]; 0xFFFFFFFF is returned otherwise): the top
+ * log2(positions) bits of key * 0x9E3779B1 mod 2^32.  key = row id, with bit 31 set for context rows.
+ * A batch uses the smallest power of two >= max(2048, 2 * references) positions, references = B * (K + 2)
+ * <= 2^28, so at most 2^29.  Host-only; exists so that the spread of home positions can be checked
+ * without a GPU.
+ */
+uint32_t ne_hash_position(uint32_t key, uint32_t positions);
 
 /*
  * Measurement hooks (instrumentation for benchmarks, not part of the method).  After

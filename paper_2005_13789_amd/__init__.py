@@ -27,7 +27,7 @@ NE_MAX_BATCH = 1 << 22
 EXPORTS = (
     "ne_create_tables", "ne_build_neg_alias", "ne_workspace_bytes", "ne_train_batch", "ne_train_block", "ne_train_block_pinned", "ne_train_walks",
     "ne_shared_workspace_bytes", "ne_train_batch_shared", "ne_train_batch_shared_static", "ne_train_batch_async", "ne_set_vertex_window", "ne_eval_loss",
-    "ne_score_pairs", "ne_set_tuning", "ne_validate_pairs", "ne_profile_enable", "ne_profile_read", "ne_destroy_tables", "ne_destroy_alias", "ne_last_error",
+    "ne_score_pairs", "ne_set_tuning", "ne_validate_pairs", "ne_hash_position", "ne_profile_enable", "ne_profile_read", "ne_destroy_tables", "ne_destroy_alias", "ne_last_error",
 )
 
 _lib = None
@@ -86,6 +86,8 @@ def lib() -> ctypes.CDLL:
     L.ne_set_tuning.restype = c.c_int
     L.ne_validate_pairs.argtypes = [vp, vp, c.c_int64, vp, vp]
     L.ne_validate_pairs.restype = c.c_int
+    L.ne_hash_position.argtypes = [c.c_uint32, c.c_uint32]
+    L.ne_hash_position.restype = c.c_uint32
     L.ne_profile_enable.argtypes = [vp, c.c_int32, c.c_int32]
     L.ne_profile_enable.restype = c.c_int
     L.ne_profile_read.argtypes = [vp, c.POINTER(c.c_double), c.POINTER(c.c_int64)]
@@ -353,6 +355,11 @@ def ne_validate_pairs(tables: Tables, pairs: torch.Tensor, bad_count: torch.Tens
     pp = _dev_ptr(pairs, torch.int32, "pairs")
     bp = _dev_ptr(bad_count, torch.int64, "bad_count")
     _check(lib().ne_validate_pairs(tables.handle, pp, int(pairs.shape[0]), bp, _stream_ptr(stream)))
+
+
+def ne_hash_position(key: int, positions: int) -> int:
+    """Home position of a row key among `positions` hash positions (host-only debug helper)."""
+    return int(lib().ne_hash_position(key & 0xFFFFFFFF, positions))
 
 
 def ne_profile_enable(tables: Tables, every_n: int, max_samples: int = 4096) -> None:

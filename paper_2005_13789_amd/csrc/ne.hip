@@ -89,7 +89,7 @@ __global__ __launch_bounds__(256) void init_tables_kernel(float4* __restrict__ X
 // ---------------------------------------------------------------------------------------------
 constexpr unsigned long long kEmptySlot = ~0ull;
 
-__device__ __forceinline__ uint32_t hash_key(uint32_t key, uint32_t mask) { return ((key * 0x9E3779B1u) >> 7) & mask; }
+__device__ __forceinline__ uint32_t hash_key(uint32_t key, uint32_t mask) { return hash_position(key, mask); }
 
 struct PrepArgs {
     const int2* pairs;    // pair mode: the batch's pairs
@@ -1945,6 +1945,12 @@ ne_status ne_set_tuning(ne_tables* t, int32_t list_cap, int32_t sweep_per_thread
     t->tune_list_cap = list_cap;
     t->tune_sweep = sweep_per_thread;
     return NE_OK;
+}
+
+uint32_t ne_hash_position(uint32_t key, uint32_t positions)
+{
+    if (positions < 2 || positions > 0x80000000u || (positions & (positions - 1)) != 0) return 0xFFFFFFFFu;
+    return hash_position(key, positions - 1);
 }
 
 ne_status ne_validate_pairs(const ne_tables* t, const int32_t* pairs_dev, int64_t B,

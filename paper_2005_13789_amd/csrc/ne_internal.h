@@ -88,6 +88,20 @@ inline void profile_end(ne_tables* t, hipStream_t st)
     if (hipEventRecord(t->ev_stop[t->ev_used], st) == hipSuccess) t->ev_used += 1;
 }
 
+// Home position of a row key in a table of mask + 1 positions (a power of two, at most 2^31): the top
+// log2(positions) bits of a Fibonacci multiplicative hash, so that every position is some key's home
+// however large the table (a fixed shift would leave tables wider than its bits mostly unreachable and
+// pile the keys into one cluster).
+__host__ __device__ __forceinline__ uint32_t hash_position(uint32_t key, uint32_t mask)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    const int shift = __clz(static_cast<int>(mask));
+#else
+    const int shift = __builtin_clz(mask);
+#endif
+    return (key * 0x9E3779B1u) >> shift;
+}
+
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 // ---------------------------------------------------------------------------------------------

@@ -79,7 +79,7 @@ struct SharedWs {
 
 // References of a batch: 2b the source row of pair b, 2b + 1 its context row, 2B + j negative j.
 // key = row | (context table ? 1 << 31 : 0).
-__device__ __forceinline__ uint32_t ref_hash(uint32_t key, uint32_t mask) { return ((key * 0x9E3779B1u) >> 9) & mask; }
+__device__ __forceinline__ uint32_t ref_hash(uint32_t key, uint32_t mask) { return hash_position(key, mask); }
 __device__ __forceinline__ unsigned long long ref_entry(uint32_t key, uint32_t ref) { return (static_cast<unsigned long long>(key) << 32) | ref; }
 constexpr uint32_t kContextKey = 0x80000000u;
 

@@ -154,16 +154,20 @@ def test_config3_sampled_rows():
 def test_maximum_batch_size():
     """One batch of NE_MAX_BATCH pairs (2^22; 29 M row references, 67 M hash positions in use) through ne_train_batch
     and a second one through ne_train_block, every element against the oracle.  A small dimension keeps the
-    per-position delta slots (capacity x dim x 4 bytes) and the oracle's time small.  The heavy tail of the
-    pairs' id distribution wraps around instead of piling up on one id: with 3.5 % of the pairs sharing one source
-    row, the hottest negative row (named 4e5 times in the batch) receives 1.5e4 identical contributions and its
-    running fp32 sum drifts by 1.6e-4 of the row (measured) - a statement about fp32 accumulation of
-    same-sign terms, not about the batch size.  The hottest row is still named 4e5 times here."""
+    per-position delta slots (capacity x dim x 4 bytes) and the oracle's time small.
+
+    The ids are heavy-tailed and clamped to the id range, so the last row collects the tail: 3.5 % of the pairs
+    name it as their source, and the hottest context row is named 4e5 times.  A row that n references of one
+    batch name has its n deltas added one by one in fp32 (atomic adds into the row's slot), so its error is
+    bounded by n * 2^-24 of the summed magnitudes, and the bound is approached when many contributions are
+    identical (same source row against the same context row: the rounding errors then all point the same way;
+    1.6e-4 of the row was measured on the hottest row here).  The bar per row is therefore max(1e-4, n_r * 2^-24):
+    1e-4 for every row named up to 1677 times, the accumulation bound beyond."""
     V, d, K, B, seed = 3_000_000, 8, 5, ne.NE_MAX_BATCH, 9
     say(f"maximum batch: B={B} V={V} d={d} K={K}; workspace {ne.ne_workspace_bytes(d, B, K) / 2**30:.1f} GiB")
     rng = np.random.default_rng(0)
     deg = (rng.pareto(1.0, V) * 3).astype(np.uint32) + 1
-    pairs = ((rng.pareto(0.9, (2 * B, 2)) * V / 40).astype(np.int64) % V).astype(np.int32)
+    pairs = np.minimum((rng.pareto(0.9, (2 * B, 2)) * V / 40).astype(np.int64), V - 1).astype(np.int32)
     t = make_tables(V, d, K, B, seed)
     t.context.copy_(torch.randn((V, d), generator=torch.Generator().manual_seed(1)).to(DEV) * 0.1)
     at = torch.empty((V, 2), dtype=torch.int32, device=DEV)
@@ -181,16 +185,24 @@ def test_maximum_batch_size():
         torch.cuda.synchronize()
         negs = oracle.sample_negatives(seed, it * B, B, K, thr, al)
         assert np.array_equal(neg.cpu().numpy(), negs)
-        oracle.train_batch(Xo, Co, pairs[it * B:(it + 1) * B], negs, 0.01)
-        ex = rowwise_rel_err(t.vertex.cpu().numpy(), Xo, floor_frac=1e-3)
-        ec = rowwise_rel_err(t.context.cpu().numpy(), Co, floor_frac=1e-3)
-        say(f"  {call}: row error X {ex:.2e} C {ec:.2e}")
-        Cg = t.context.cpu().numpy()
-        err = np.abs(Cg.astype(np.float64) - Co).max(axis=1); den = np.abs(Co).max(axis=1)
-        worst = int(np.argmax(err / np.maximum(den, 1e-3 * den.max())))
-        cnt = int((pairs[it * B:(it + 1) * B, 1] == worst).sum() + (negs == worst).sum())
-        say(f"  worst C row {worst}: named {cnt} times, |row| {den[worst]:.3e}, abs err {err[worst]:.3e}, table max {den.max():.3e}")
-        assert ex <= 1e-4 and ec <= 1e-4
+        pn = pairs[it * B:(it + 1) * B]
+        oracle.train_batch(Xo, Co, pn, negs, 0.01)
+        named = {"X": np.bincount(pn[:, 0], minlength=V),
+                 "C": np.bincount(pn[:, 1], minlength=V) + np.bincount(negs.reshape(-1), minlength=V)}
+        for name, got, want in (("X", t.vertex.cpu().numpy(), Xo), ("C", t.context.cpu().numpy(), Co)):
+            err = np.abs(got.astype(np.float64) - want).max(axis=1)
+            den = np.abs(want.astype(np.float64)).max(axis=1)
+            live = den > 0
+            rel = np.zeros(V); rel[live] = err[live] / den[live]
+            n = named[name]
+            bar = np.maximum(1e-4, n * 2.0**-24)
+            worst = int(np.argmax(rel / bar))
+            few = n <= 1677
+            say(f"  {call} {name}: rows named <= 1677 times: max row error {rel[few].max():.2e}; oftener ({int((~few).sum())} rows, "
+                f"up to {int(n.max())} times): max {rel[~few].max() if (~few).any() else 0.0:.2e}; closest to its bar: row {worst} "
+                f"named {int(n[worst])} times, error {rel[worst]:.2e} of bar {bar[worst]:.2e}")
+            assert (rel <= bar).all()
+            assert rel[few].max() <= 1e-4
         t.vertex.copy_(torch.from_numpy(Xo)); t.context.copy_(torch.from_numpy(Co))
 
 
@@ -300,7 +312,7 @@ def test_config2_walk_batches_full_compare():
         neg = np.ascontiguousarray(neg_all[sample])
         assert np.array_equal(got[first + sample], neg)
         oracle.train_batch(Xo, Co, pairs, neg, lrs[b])
-    ex = rowwise_rel_err(t.vertex.cpu().numpy(), Xo, floor_frac=1e-3)
-    ec = rowwise_rel_err(t.context.cpu().numpy(), Co, floor_frac=1e-3)
+    ex = rowwise_rel_err(t.vertex.cpu().numpy(), Xo)
+    ec = rowwise_rel_err(t.context.cpu().numpy(), Co)
     say(f"  rowwise err X {ex:.2e} C {ec:.2e}")
     assert ex <= 3e-4 and ec <= 3e-4       # three batches

@@ -61,7 +61,7 @@ def test_negative_ids_bit_exact(d, K, B, sample_base):
     assert np.array_equal(got, want)
 
 
-def run_case(V, d, K, B, n_batches, seed, lr0=0.025, scale=None, base=0, n_alias=None, tol=1e-4, floor=0.0):
+def run_case(V, d, K, B, n_batches, seed, lr0=0.025, scale=None, base=0, n_alias=None, tol=1e-4):
     """Train n_batches on random pairs from both sides; returns the per-batch records."""
     rng = np.random.default_rng(seed + 17)
     n_alias = V if n_alias is None else n_alias
@@ -87,14 +87,16 @@ def run_case(V, d, K, B, n_batches, seed, lr0=0.025, scale=None, base=0, n_alias
         neg_o = oracle.sample_negatives(seed, sample_base, nb, K, thr, alias, base) if K > 0 else np.zeros((nb, 0), np.int32)
         loss_g = m.loss_sum(pd, sample_base)
         loss_o = oracle.eval_loss(Xo, Co, pairs, neg_o)
-        assert abs(loss_g - loss_o) <= 0.01 * abs(loss_o), (t, loss_g, loss_o)
+        # one evaluation at identical tables (batch 0) is fp32 terms against fp64: 1e-5; later batches compare
+        # two trajectories (each side evolves its own tables), where the bar is the loss curve's 1 %
+        assert abs(loss_g - loss_o) <= (1e-5 if t == 0 else 0.01) * abs(loss_o), (t, loss_g, loss_o)
         Xb, Cb = (m.host_tables() if t == 0 else (None, None))
         neg_g = m.train(pd, lr, sample_base)
         assert np.array_equal(neg_g, neg_o), f"negative ids differ in batch {t}"
         oracle.train_batch(Xo, Co, pairs, neg_o, lr)
         if t == 0:
             Xg, Cg = m.host_tables()
-            ex, ec = rowwise_rel_err(Xg, Xo, floor), rowwise_rel_err(Cg, Co, floor)
+            ex, ec = rowwise_rel_err(Xg, Xo), rowwise_rel_err(Cg, Co)
             say(f"  batch 0: rowwise err X {ex:.2e} C {ec:.2e}")
             assert ex <= tol and ec <= tol
             touchedX = np.zeros(V, bool); touchedX[pairs[:, 0]] = True
@@ -170,6 +172,27 @@ def test_config1_100_batches():
     assert ex <= 1e-3 and ec <= 1e-3
     assert table_rel_err(Xg, Xo) <= 1e-3 and table_rel_err(Cg, Co) <= 1e-3
     assert losses[-1][0] < losses[0][0]
+
+
+@pytest.mark.parametrize("V,d,K,B,scale", [(5000, 128, 5, 4096, 0.3), (3000, 512, 10, 700, 0.1), (800, 64, 0, 333, 0.5),
+                                           (2000, 256, 31, 257, 0.2), (4000, 100, 5, 1, 1.0), (6000, 128, 5, 65536, 0.4)])
+def test_eval_loss_single_call_precision(V, d, K, B, scale):
+    """ne_eval_loss at tables identical to the oracle's: fp32 dot products and softplus terms, fp64 sum,
+    against fp64 throughout.  A term's error is ~d * 2^-24 of its score plus one ulp of the term and the
+    errors of the B(K+1) terms do not line up, so one call sits near 1e-7; the bar is 1e-5.  Scores reach
+    several units here (large |score| exercises both branches of the stable softplus)."""
+    say(f"eval_loss precision V={V} d={d} K={K} B={B}")
+    rng = np.random.default_rng(V + d)
+    deg = (rng.pareto(1.0, V) * 2).astype(np.uint32) + 1
+    X = rng.normal(0, scale, (V, d)).astype(np.float32)
+    C = rng.normal(0, scale, (V, d)).astype(np.float32)
+    m = GpuModel(V, d, 3, deg, K, B, X=X, C=C)
+    pairs = rng.integers(0, V, (B, 2)).astype(np.int32)
+    neg_o = oracle_negatives(3, 99, B, K, deg)
+    lg = m.loss_sum(torch.from_numpy(pairs).cuda(), 99)
+    lo = oracle.eval_loss(X, C, pairs, neg_o)
+    say(f"  loss/pair {lo / B:.4f}, relative difference {abs(lg - lo) / lo:.2e}")
+    assert abs(lg - lo) <= 1e-5 * lo
 
 
 def test_empty_batch_and_validate():

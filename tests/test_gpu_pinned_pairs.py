@@ -1,9 +1,11 @@
 """Sample batches prefetched from pinned host memory while training (Sec. IV-A pipeline, single-GPU part):
-ne_train_block_pinned must give the result of ne_train_block on resident pairs."""
+ne_train_block_pinned against the CPU oracle on the same batches (negatives bit-exact, tables row-wise within
+1e-4 per batch), and against ne_train_block on resident pairs."""
 import numpy as np
 import pytest
 import torch
 
+import oracle
 import paper_2005_13789_amd as ne
 from parity_util import rowwise_rel_err
 
@@ -33,6 +35,7 @@ def test_pinned_block_equals_resident_block(n):
     nb = -(-n // B)
     lrs = [0.02 / (1 + 0.1 * b) for b in range(nb)]
     resident, pinned = make(V, d, B, K, 4), make(V, d, B, K, 4)
+    Xo, Co = pinned.vertex.cpu().numpy(), pinned.context.cpu().numpy()
     neg_r = torch.empty((n, K), dtype=torch.int32, device=DEV)
     neg_p = torch.empty((n, K), dtype=torch.int32, device=DEV)
     ne.ne_train_block(resident, alias, pairs.to(DEV), B, K, lrs, 500, neg_r)
@@ -40,9 +43,21 @@ def test_pinned_block_equals_resident_block(n):
     ne.ne_train_block_pinned(pinned, alias, pairs.pin_memory(), B, K, lrs, 500, staging, neg_p)
     torch.cuda.synchronize()
     assert torch.equal(neg_r, neg_p)
-    ex = rowwise_rel_err(pinned.vertex.cpu().numpy(), resident.vertex.cpu().numpy(), floor_frac=1e-3)
-    ec = rowwise_rel_err(pinned.context.cpu().numpy(), resident.context.cpu().numpy(), floor_frac=1e-3)
+    ex = rowwise_rel_err(pinned.vertex.cpu().numpy(), resident.vertex.cpu().numpy())
+    ec = rowwise_rel_err(pinned.context.cpu().numpy(), resident.context.cpu().numpy())
     print(f"  row error X {ex:.2e} C {ec:.2e}", flush=True)
     assert ex <= 1e-5 and ec <= 1e-5
+    # the oracle on the same batches
+    thr, al, _ = oracle.build_alias(deg)
+    pn = pairs.numpy()
+    for b in range(nb):
+        p = np.ascontiguousarray(pn[b * B:(b + 1) * B])
+        neg = oracle.sample_negatives(4, 500 + b * B, p.shape[0], K, thr, al)
+        assert np.array_equal(neg_p[b * B:b * B + p.shape[0]].cpu().numpy(), neg)
+        oracle.train_batch(Xo, Co, p, neg, lrs[b])
+    ox = rowwise_rel_err(pinned.vertex.cpu().numpy(), Xo)
+    oc = rowwise_rel_err(pinned.context.cpu().numpy(), Co)
+    print(f"  against the oracle after {nb} batches: row error X {ox:.2e} C {oc:.2e}", flush=True)
+    assert ox <= min(1e-4 * nb, 1e-3) and oc <= min(1e-4 * nb, 1e-3)
     with pytest.raises(TypeError):
         ne.ne_train_block_pinned(pinned, alias, pairs, B, K, lrs, 500, staging)       # pageable host memory

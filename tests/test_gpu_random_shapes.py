@@ -79,8 +79,8 @@ def test_random_shape(i):
         sl = slice(b * B, min((b + 1) * B, n_pairs))
         oracle.train_batch(Xo, Co, np.ascontiguousarray(pairs[sl]), np.ascontiguousarray(neg[sl]), lrs[b])
     for name, t in (("block", tb), ("batch", t1)):
-        ex = rowwise_rel_err(t.vertex.cpu().numpy(), Xo, floor_frac=1e-3)
-        ec = rowwise_rel_err(t.context.cpu().numpy(), Co, floor_frac=1e-3)
+        ex = rowwise_rel_err(t.vertex.cpu().numpy(), Xo)
+        ec = rowwise_rel_err(t.context.cpu().numpy(), Co)
         assert ex <= tol and ec <= tol, (name, ex, ec)
 
     # walks of the same shape family
@@ -103,6 +103,6 @@ def test_random_shape(i):
         first = b * wpb * L * window
         neg_all = oracle.sample_negatives(seed, base + first, part.shape[0] * L * window, K, thr, al)
         oracle.train_batch(Xo, Co, wp, np.ascontiguousarray(neg_all[sample]), lrs[b])
-    ex = rowwise_rel_err(tw.vertex.cpu().numpy(), Xo, floor_frac=1e-3)
-    ec = rowwise_rel_err(tw.context.cpu().numpy(), Co, floor_frac=1e-3)
+    ex = rowwise_rel_err(tw.vertex.cpu().numpy(), Xo)
+    ec = rowwise_rel_err(tw.context.cpu().numpy(), Co)
     assert ex <= tol and ec <= tol, ("walks", ex, ec)

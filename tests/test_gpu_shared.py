@@ -4,7 +4,10 @@ Both sides round the gathered rows and the coefficients G to bfloat16 in the sam
 accumulates the dense products in fp32 on the matrix cores, the oracle in fp64.  A last-bit difference in
 a score can move one G entry by one bf16 ulp (2^-8 relative) on one side only; an entry is one of N terms
 of a delta (N >= 128), i.e. at most 2^-8 / 128 = 3e-5 of it per flipped entry, so the bar is stated on the
-update itself: |dG - dO|_inf <= 2e-4 |dO|_inf per table, and the tables within 1e-4 of the table maximum.  Negative ids are bit-exact.
+update itself: |dG - dO|_inf <= 2e-4 |dO|_inf per table, and the tables within 1e-4 of the table maximum.
+Row by row the same flip weighs more where a row's terms partly cancel (the flipped term is 2^-8 of itself,
+not of the row's sum): per row |dG_r - dO_r|_inf <= 2e-3 |dO_r|_inf (measured <= 3e-4).  Negative ids are
+bit-exact.
 """
 import numpy as np
 import pytest
@@ -25,6 +28,15 @@ def delta_err(before, got, want):
     dg = got.astype(np.float64) - before.astype(np.float64)
     do = want.astype(np.float64) - before.astype(np.float64)
     return np.abs(dg - do).max() / max(np.abs(do).max(), 1e-30)
+
+
+def rowwise_delta_err(before, got, want):
+    """max over rows whose update is not zero of |dG_r - dO_r|_inf / |dO_r|_inf."""
+    dg = got.astype(np.float64) - before.astype(np.float64)
+    do = want.astype(np.float64) - before.astype(np.float64)
+    num, den = np.abs(dg - do).max(axis=1), np.abs(do).max(axis=1)
+    live = den > 0
+    return float((num[live] / den[live]).max()) if live.any() else 0.0
 
 
 @pytest.mark.parametrize("V,d,B,N,batches", [(3000, 256, 1000, 256, 3), (2000, 128, 700, 128, 2), (1500, 64, 100, 128, 2),
@@ -62,8 +74,10 @@ def test_shared_negative_step(V, d, B, N, batches):
         ex, ec = delta_err(Xb, Xg, Xo), delta_err(Cb, Cg, Co)
         tx = np.abs(Xg - Xo).max() / np.abs(Xo).max()
         tc = np.abs(Cg - Co).max() / np.abs(Co).max()
-        say(f"  batch {it}: delta err X {ex:.2e} C {ec:.2e}; table err X {tx:.2e} C {tc:.2e}; loss {loss_o / B:.4f}")
+        rx, rc = rowwise_delta_err(Xb, Xg, Xo), rowwise_delta_err(Cb, Cg, Co)
+        say(f"  batch {it}: delta err X {ex:.2e} C {ec:.2e}; row-wise delta err X {rx:.2e} C {rc:.2e}; table err X {tx:.2e} C {tc:.2e}; loss {loss_o / B:.4f}")
         assert ex <= 2e-4 and ec <= 2e-4
+        assert rx <= 2e-3 and rc <= 2e-3
         assert tx <= 1e-4 and tc <= 1e-4
         touched_x = np.zeros(V, bool); touched_x[pairs[:, 0]] = True
         touched_c = np.zeros(V, bool); touched_c[pairs[:, 1]] = True; touched_c[negs] = True

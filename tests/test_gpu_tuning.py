@@ -55,7 +55,7 @@ def test_pairs_with_tuning(V, d, K, B, n_pairs, list_cap, sweep):
     for b in range(n_batches):
         oracle.train_batch(Xo, Co, pairs[b * B:(b + 1) * B], neg[b * B:(b + 1) * B], lrs[b])
     Xg, Cg = t.vertex.cpu().numpy(), t.context.cpu().numpy()
-    ex, ec = rowwise_rel_err(Xg, Xo, floor_frac=1e-3), rowwise_rel_err(Cg, Co, floor_frac=1e-3)
+    ex, ec = rowwise_rel_err(Xg, Xo), rowwise_rel_err(Cg, Co)
     say(f"  row error X {ex:.2e} C {ec:.2e}")
     assert ex <= 1e-4 * n_batches and ec <= 1e-4 * n_batches
     named_x = np.zeros(V, bool); named_x[pairs[:, 0]] = True
@@ -66,8 +66,8 @@ def test_pairs_with_tuning(V, d, K, B, n_pairs, list_cap, sweep):
     ne.ne_train_block(t, alias, torch.from_numpy(pairs[:B]).to(DEV), B, K, lrs[:1], base)
     torch.cuda.synchronize()
     oracle.train_batch(Xo, Co, pairs[:B], neg[:B], lrs[0])
-    assert rowwise_rel_err(t.vertex.cpu().numpy(), Xo, floor_frac=1e-3) <= 1e-4 * (n_batches + 1)
-    assert rowwise_rel_err(t.context.cpu().numpy(), Co, floor_frac=1e-3) <= 1e-4 * (n_batches + 1)
+    assert rowwise_rel_err(t.vertex.cpu().numpy(), Xo) <= 1e-4 * (n_batches + 1)
+    assert rowwise_rel_err(t.context.cpu().numpy(), Co) <= 1e-4 * (n_batches + 1)
 
 
 @pytest.mark.parametrize("list_cap,sweep", TUNINGS)
@@ -95,8 +95,8 @@ def test_walks_with_tuning(V, d, K, n, L, window, wpb, list_cap, sweep):
     ne.ne_train_walks(t, alias, torch.from_numpy(walks).to(DEV), wpb, window, K, lrs, sample_base)
     torch.cuda.synchronize()
     oracle_run(Xo, Co, walks, wpb, window, K, lrs, seed, sample_base, thr, al)
-    ex = rowwise_rel_err(t.vertex.cpu().numpy(), Xo, floor_frac=1e-3)
-    ec = rowwise_rel_err(t.context.cpu().numpy(), Co, floor_frac=1e-3)
+    ex = rowwise_rel_err(t.vertex.cpu().numpy(), Xo)
+    ec = rowwise_rel_err(t.context.cpu().numpy(), Co)
     say(f"  row error X {ex:.2e} C {ec:.2e}")
     assert ex <= 1e-4 * n_batches and ec <= 1e-4 * n_batches
 
@@ -132,7 +132,7 @@ def test_exact_multiplicities_around_the_list_capacity(list_cap, d):
         ne.ne_train_batch(t, None, torch.from_numpy(pairs).to(DEV), K, 0.05, 0)
         torch.cuda.synchronize()
         oracle.train_batch(Xo, Co, pairs, np.zeros((B, 0), np.int32), 0.05)
-        ex = rowwise_rel_err(t.vertex.cpu().numpy(), Xo, floor_frac=1e-3)
-        ec = rowwise_rel_err(t.context.cpu().numpy(), Co, floor_frac=1e-3)
+        ex = rowwise_rel_err(t.vertex.cpu().numpy(), Xo)
+        ec = rowwise_rel_err(t.context.cpu().numpy(), Co)
         say(f"  batch {rep}: row error X {ex:.2e} C {ec:.2e}")
         assert ex <= 1e-5 * (rep + 1) and ec <= 1e-5 * (rep + 1)

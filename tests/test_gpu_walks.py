@@ -92,7 +92,7 @@ def test_walks_match_oracle(V, d, K, n, L, window, wpb):
             assert np.array_equal(got[s], row), f"negatives of sample {s}"
         assert np.all(got[~exists] == -7)                     # rows of samples that do not exist are untouched
     Xg, Cg = t.vertex.cpu().numpy(), t.context.cpu().numpy()
-    ex, ec = rowwise_rel_err(Xg, Xo, floor_frac=1e-3), rowwise_rel_err(Cg, Co, floor_frac=1e-3)
+    ex, ec = rowwise_rel_err(Xg, Xo), rowwise_rel_err(Cg, Co)
     say(f"  {len(negs)} samples; row error X {ex:.2e} C {ec:.2e}")
     assert ex <= 1e-4 * n_batches and ec <= 1e-4 * n_batches
     same_x = np.all(Xo.view(np.uint32) == Xb.view(np.uint32), axis=1)
@@ -126,8 +126,8 @@ def test_walks_equal_pairs_when_sample_indices_agree():
         pairs = np.ascontiguousarray(np.stack([walks[r, :-1], walks[r, 1:]], axis=1).astype(np.int32))
         ne.ne_train_batch(tp, alias, torch.from_numpy(pairs).to(DEV), K, 0.03, r * L)
     torch.cuda.synchronize()
-    ex = rowwise_rel_err(tw2.vertex.cpu().numpy(), tp.vertex.cpu().numpy(), floor_frac=1e-3)
-    ec = rowwise_rel_err(tw2.context.cpu().numpy(), tp.context.cpu().numpy(), floor_frac=1e-3)
+    ex = rowwise_rel_err(tw2.vertex.cpu().numpy(), tp.vertex.cpu().numpy())
+    ec = rowwise_rel_err(tw2.context.cpu().numpy(), tp.context.cpu().numpy())
     say(f"  per-walk batches: walks vs pairs row error X {ex:.2e} C {ec:.2e}")
     assert ex <= 1e-5 and ec <= 1e-5
     # and batching matters: all walks in one batch is a different (still exact) step
