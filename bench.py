@@ -35,10 +35,22 @@ import workloads as wl  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per train-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see
-# profiles/), scaled by the factor a plain copy kernel of known size reads on the same counters.
-# None = not measured for that workload.
-TRAFFIC_BYTES_PER_LAUNCH = {"c1": None, "c2": None, "c3": 554.7e6, "c4": None, "c5": None}
+# HBM bytes per launch of the dominant kernel come from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summaries
+# under profiles/ (each scaled there by what the same counter reads for a plain copy of known size): the line
+# "TRAFFIC_BYTES_PER_LAUNCH <kernel> <bytes>" of profiles/<kernel>_<workload>_hbm_counters.txt.
+def traffic_bytes_per_launch(kernel: str, workload: str):
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_hbm_counters.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) >= 3 and parts[0] == "TRAFFIC_BYTES_PER_LAUNCH" and parts[1] == kernel:
+                    return float(parts[2])
+    except OSError:
+        pass
+    return None
+
+
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 WORKLOADS = {
@@ -100,7 +112,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="c3", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--repeats", type=int, default=5,
+                    help="the timed region is run this many times, tables initialised again each time; the median is reported")
     ap.add_argument("--per-batch", action="store_true", help="one library call per batch (no fused prepare)")
+    ap.add_argument("--per-run", action="store_true", help="one ne_train_block call per bucket run instead of one ne_train_runs call")
     ap.add_argument("--mode", default="sync", choices=["sync", "async"],
                     help="sync: exact minibatch-synchronous step (the benchmark); async: unsynchronised per-sample mode")
     ap.add_argument("--cpu-batches", type=int, default=0, help="oracle batches to time (0 = auto)")
@@ -155,11 +170,18 @@ def main():
     N = w.get("shared_negatives", 0)
     if N:
         workspace = torch.empty(ne.ne_shared_workspace_bytes(d, B, N), dtype=torch.uint8, device=dev)
-        tables = ne.ne_create_tables(vertex, context, seed, init=True)
     else:
         workspace = torch.empty(ne.ne_workspace_bytes(d, B, K), dtype=torch.uint8, device=dev)
-        tables = ne.ne_create_tables(vertex, context, seed, init=True, max_batch=B, max_negatives=K, workspace=workspace)
-        apply_tuning(args, tables)
+
+    def fresh_tables():
+        """Both tables initialised again on the device (vertex uniform, context zero), workspace cleared."""
+        if N:
+            return ne.ne_create_tables(vertex, context, seed, init=True)
+        t = ne.ne_create_tables(vertex, context, seed, init=True, max_batch=B, max_negatives=K, workspace=workspace)
+        apply_tuning(args, t)
+        return t
+
+    tables = fresh_tables()
     # one alias table per context block (a GPU's context partition is fixed; negatives come from it)
     block = bp.block_rows
     deg_host = degree.to(torch.int64).clamp_(max=2**32 - 1).cpu().numpy().astype(np.uint32)
@@ -180,10 +202,23 @@ def main():
         pairs_host = pairs.cpu().pin_memory()
         staging = torch.empty((3, B, 2), dtype=torch.int32, device=dev)
 
+    def bucket_runs(first, last):
+        """Batches [first, last) as runs: consecutive batches of one (src-block, ctx-block) bucket."""
+        runs, i = [], first
+        while i < last:
+            s, n, bi, bj = sched[i]
+            k = i + 1
+            while k < last and sched[k][2:] == (bi, bj) and sched[k][0] == sched[k - 1][0] + B:
+                k += 1
+            runs.append((i, k, s, bj))
+            i = k
+        return runs
+
     def run(first, last):
-        """Batches [first, last).  Consecutive batches of one (src-block, ctx-block) bucket go to the
-        library as one ne_train_block call (the id-only work of batch i+1 then rides in the kernels
-        of batch i); --per-batch calls ne_train_batch once per batch instead."""
+        """Batches [first, last).  The exact step goes to the library as one ne_train_runs call: the runs of
+        consecutive batches of one (src-block, ctx-block) bucket, in the order of the schedule, so that the
+        id-only work of every batch but the first rides in the kernels of the batch before it.  --per-run makes
+        one ne_train_block call per bucket run, --per-batch one ne_train_batch call per batch."""
         i = first
         while N and i < last:          # shared-negative mode: one call per batch
             s, n, _, bj = sched[i]
@@ -193,49 +228,76 @@ def main():
             s, n, _, bj = sched[i]
             ne.ne_train_batch_async(tables, aliases[bj], pairs[s:s + n], K, float(lrs[i]), i * B)
             i += 1
-        while i < last:
-            s, n, bi, bj = sched[i]
-            k = i + 1
-            if not args.per_batch:
-                while k < last and sched[k][2:] == (bi, bj) and sched[k][0] == sched[k - 1][0] + B:
-                    k += 1
-            count = k - i
-            if pairs_host is not None:
-                ne.ne_train_block_pinned(tables, aliases[bj], pairs_host[s:s + count * B], B, K, lrs[i:k], i * B, staging)
-            else:
-                ne.ne_train_block(tables, aliases[bj], pairs[s:s + count * B], B, K, lrs[i:k], i * B)
-            i = k
+        if i >= last:
+            return
+        if args.per_batch:
+            for j in range(i, last):
+                s, n, _, bj = sched[j]
+                ne.ne_train_batch(tables, aliases[bj], pairs[s:s + n], K, float(lrs[j]), j * B)
+        elif pairs_host is not None:
+            for (a, b, s, bj) in bucket_runs(i, last):
+                ne.ne_train_block_pinned(tables, aliases[bj], pairs_host[s:s + (b - a) * B], B, K, lrs[a:b], a * B, staging)
+        elif args.per_run:
+            for (a, b, s, bj) in bucket_runs(i, last):
+                ne.ne_train_block(tables, aliases[bj], pairs[s:s + (b - a) * B], B, K, lrs[a:b], a * B)
+        else:
+            ne.ne_train_runs(tables, [(aliases[bj], pairs[s:s + (b - a) * B], a * B) for (a, b, s, bj) in bucket_runs(i, last)],
+                             B, K, lrs[i:last])
 
-    torch.cuda.synchronize()
-    run(0, args.warmup)
-    torch.cuda.synchronize()
-    ne.ne_profile_enable(tables, 4, args.steps // 4 + 2)
-    t_start = time.perf_counter()
-    run(args.warmup, n_batches)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t_start
-    kern_ms, kern_n = ne.ne_profile_read(tables)
-    ne.ne_profile_enable(tables, 0, 0)
+    # args.repeats times: tables initialised again, warm-up, then the timed steps; the median repeat is reported
+    samples = []
+    for rep in range(args.repeats):
+        if rep > 0:
+            tables = fresh_tables()
+        torch.cuda.synchronize()
+        run(0, args.warmup)
+        torch.cuda.synchronize()
+        ne.ne_profile_enable(tables, 4, args.steps // 4 + 2)
+        t_start = time.perf_counter()
+        run(args.warmup, n_batches)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t_start
+        kern_ms, kern_n = ne.ne_profile_read(tables)
+        ne.ne_profile_enable(tables, 0, 0)
+        samples.append((elapsed, kern_ms / max(kern_n, 1), kern_n))
+        log(f"repeat {rep}: {args.steps * B / elapsed / 1e6:.1f} M pairs/s, {elapsed / args.steps * 1e6:.1f} us/step, "
+            f"dominant kernel {kern_ms / max(kern_n, 1) * 1e3:.1f} us")
+    samples.sort()
+    elapsed, avg_kernel_ms, kern_n = samples[len(samples) // 2]
 
     pairs_per_s = args.steps * B / elapsed
-    avg_kernel_ms = kern_ms / max(kern_n, 1)
+    copy_GBps = copy_ceiling(dev)
     if N:
         # two gathered rows per pair and the N shared rows per batch, read and written once; ids
         bpp = 2 * (2 * B + N) * 4 * d / B + 8
         flops = 2 * 2.0 * B * N * d          # S and dX products of the scores kernel
+        step_flops = 3 * 2.0 * B * N * d     # all three dense products of a step
         achieved = flops / (avg_kernel_ms * 1e-3) / 1e12 if kern_n else None
+        step_achieved = step_flops * pairs_per_s / B / 1e12
         roofline = {"bound": "mfma", "kernel": "scores_kernel", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": (achieved / MFMA_BF16_PEAK_TFLOPS) if achieved else None, "traffic": None,
-                    "flops_per_launch": flops, "avg_kernel_ms": avg_kernel_ms, "kernel_samples": kern_n}
+                    "unit": "TFLOP/s", "frac": (achieved / MFMA_BF16_PEAK_TFLOPS) if achieved else None,
+                    "traffic": traffic_bytes_per_launch("scores_kernel", name),
+                    "flops_per_launch": flops, "avg_kernel_ms": avg_kernel_ms, "kernel_samples": kern_n,
+                    "step_achieved": step_achieved, "step_frac": step_achieved / MFMA_BF16_PEAK_TFLOPS,
+                    "step_hbm_GBps": pairs_per_s * bpp / 1e9, "step_hbm_frac": pairs_per_s * bpp / 1e9 / HBM_PEAK_GBS}
         call = "ne_train_batch_shared per step"
     else:
         bpp = algorithmic_bytes_per_pair(d, K)
+        kernel = "async_kernel" if args.mode == "async" else "train_kernel"
         achieved = (bpp * B) / (avg_kernel_ms * 1e-3) / 1e9 if kern_n else None
-        roofline = {"bound": "hbm", "kernel": "async_kernel" if args.mode == "async" else "train_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        step_achieved = pairs_per_s * bpp / 1e9
+        roofline = {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
-                    "traffic": TRAFFIC_BYTES_PER_LAUNCH[name] if args.mode == "sync" else None, "bytes_per_launch": bpp * B,
-                    "avg_kernel_ms": avg_kernel_ms, "kernel_samples": kern_n}
-        call = "ne_train_batch per step" if args.per_batch else "ne_train_block per bucket run"
+                    "traffic": traffic_bytes_per_launch(kernel, name), "bytes_per_launch": bpp * B,
+                    "avg_kernel_ms": avg_kernel_ms, "kernel_samples": kern_n,
+                    # the whole step (every launch of a batch) on algorithmic bytes: the headline fraction
+                    "step_achieved": step_achieved, "step_frac": step_achieved / HBM_PEAK_GBS,
+                    "copy_ceiling_GBps": copy_GBps, "step_frac_of_copy_ceiling": step_achieved / copy_GBps}
+        call = "ne_train_runs, one call per timed region"
+        if args.per_run:
+            call = "ne_train_block per bucket run"
+        if args.per_batch:
+            call = "ne_train_batch per step"
         if pairs_host is not None:
             call = "ne_train_block_pinned per bucket run (pairs prefetched from pinned host memory inside the launches)"
         if args.mode == "async":
@@ -247,6 +309,7 @@ def main():
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "repeats": args.repeats,
         "ms_per_step": elapsed / args.steps * 1e3,
         "higher_is_better": True,
         "scaling": "weak",
@@ -254,13 +317,28 @@ def main():
         "dtype": "bf16" if N else "f32",
         "data": "synthetic",
         "config": {"workload": name, "nodes": V, "dim": d, "negatives": N if N else K, "batch": B,
-                   "block_grid": f"{grid}x{grid}", "call": call, "end_to_end_GBps": pairs_per_s * bpp / 1e9},
+                   "block_grid": f"{grid}x{grid}", "call": call, "end_to_end_GBps": pairs_per_s * bpp / 1e9,
+                   "pairs_per_s_of_each_repeat": [args.steps * B / e for e, _, _ in samples]},
         "roofline": roofline,
     }
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, deg_host, bp, sched, args.cpu_batches)
     print(json.dumps(result), flush=True)
+
+
+def copy_ceiling(dev) -> float:
+    """GB/s (read + write) of a plain 1 GiB device-to-device copy: the practical ceiling beside the datasheet peak."""
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(10):
+        dst.copy_(src)
+    stop.record()
+    torch.cuda.synchronize()
+    return 10 * 2 * src.numel() * 4 / (start.elapsed_time(stop) * 1e-3) / 1e9
 
 
 def walks_scenario(args, dev):
@@ -445,8 +523,8 @@ def cpu_baseline(w, deg_host, bp, sched, n_cpu_batches):
     t0 = time.perf_counter()
     run(0, p0)
     first = time.perf_counter() - t0
-    if n_cpu_batches <= 0:               # size the sample to about 15 s of oracle work
-        n_cpu_batches = int(max(1, min(256, 15.0 / max(first, 1e-3))))
+    if n_cpu_batches <= 0:               # size the one-thread sample to about 10 s of oracle work
+        n_cpu_batches = int(max(1, min(256, 10.0 / max(first, 1e-3))))
     batches = [batch(i) for i in range(1, n_cpu_batches + 1)]
     t0 = time.perf_counter()
     done = 0
@@ -457,8 +535,28 @@ def cpu_baseline(w, deg_host, bp, sched, n_cpu_batches):
     sample = f"{n_cpu_batches} batches of {B} pairs"
     if V != fold:
         sample += f" on a row-folded replica (ids mod {fold})"
-    return {"value": done / dt, "unit": "pairs/s", "cores": 1, "kind": "oracle", "sample": sample,
-            "seconds": dt, "host_cpus": os.cpu_count()}
+    one = {"value": done / dt, "unit": "pairs/s", "cores": 1, "kind": "oracle", "sample": sample,
+           "seconds": dt, "host_cpus": os.cpu_count()}
+    if N:
+        return one                       # the shared-negative oracle has no threaded form
+    # the same step shared out over the host cores this job may use (per-thread fp64 sums, added in thread order)
+    threads = max(1, min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16"))))
+    negs = [oracle.sample_negatives(seed, i * B, p.shape[0], K, thr, alias, 0) for i, p in enumerate(batches, start=1)]
+    oracle.train_batch_threads(X, C, batches[0], negs[0], 0.025, threads)     # untimed: the threads' pools get their pages
+    t0 = time.perf_counter()
+    oracle.train_batch_threads(X, C, batches[0], negs[0], 0.025, threads)
+    one_pass = (time.perf_counter() - t0) * len(batches)
+    reps = int(max(1, min(32, 10.0 / max(one_pass, 1e-3))))                   # about 10 s in all
+    t0 = time.perf_counter()
+    done_mt = 0
+    for _ in range(reps):
+        for p, neg in zip(batches, negs):
+            oracle.train_batch_threads(X, C, p, neg, 0.025, threads)
+            done_mt += p.shape[0]
+    dt_mt = time.perf_counter() - t0
+    return {"value": done_mt / dt_mt, "unit": "pairs/s", "cores": threads, "kind": "oracle",
+            "sample": f"{reps} x {sample}, pairs shared out over {threads} threads (oracle_train_batch_threads; negatives drawn beforehand)",
+            "seconds": dt_mt, "host_cpus": os.cpu_count(), "one_thread": one}
 
 
 if __name__ == "__main__":

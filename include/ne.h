@@ -109,7 +109,10 @@ ne_status ne_build_neg_alias(ne_alias** out, const uint32_t* degree_host, int64_
  * row many times).  Up to n of about 1700 that is inside a relative error of 1e-4 per row; a hub row that
  * tens of thousands of samples of one batch name can exceed it (1.7e-4 measured at n = 4e5).
  * Calls on one handle must be ordered by the stream and must not overlap: the handle's workspace
- * carries state from one call to the next.  Errors: NE_ERR_ARG, NE_ERR_STATE, NE_ERR_HIP.
+ * carries state from one call to the next.  Errors: NE_ERR_ARG, NE_ERR_STATE, NE_ERR_HIP.  After
+ * NE_ERR_HIP from a training call (a kernel launch failed part-way through its batches) the handle stays
+ * usable: the next training call clears the workspace again before it starts; the tables may hold the
+ * batches that were enqueued before the failure and part of the failing one.
  */
 ne_status ne_train_batch(ne_tables* tables, const ne_alias* alias, const int32_t* pairs_dev, int64_t B,
                          int32_t K, float lr, uint64_t sample_base, int32_t* neg_out_dev,
@@ -131,6 +134,30 @@ ne_status ne_train_batch(ne_tables* tables, const ne_alias* alias, const int32_t
 ne_status ne_train_block(ne_tables* tables, const ne_alias* alias, const int32_t* pairs_dev,
                          int64_t n_pairs, int64_t B, int32_t K, const float* lr_host,
                          uint64_t sample_base, int32_t* neg_out_dev, void* hip_stream);
+
+/*
+ * Train on a sequence of runs, each a run of consecutive batches as in ne_train_block on its own sample
+ * block with its own negative-sampling table: what one GPU does over an epoch when it visits its sample
+ * blocks one after the other (Sec. III-C, 2D partition of the samples).  Same result as one
+ * ne_train_block call per run, in order; the call exists because the id-only work of a run's first batch
+ * then rides in the kernels of the previous run's last batch, where separate calls would launch it on its
+ * own (two extra kernel launches per run).
+ *   runs_host : host, ne_run[n_runs], read during the call only.  Per run: alias (may be NULL if K == 0),
+ *               pairs_dev (device, int32[n_pairs][2], 8-byte aligned), n_pairs (0 = the run is skipped),
+ *               sample_base (sample index of the run's first pair), neg_out_dev (NULL, or device
+ *               int32[n_pairs][K]).  Batches never straddle two runs: the last batch of a run may be short.
+ *   lr_host   : host, one float per batch, the runs' batches in order (sum over runs of ceil(n_pairs / B)).
+ * Other arguments, semantics and errors as for ne_train_block.  n_runs == 0 is a no-op.
+ */
+typedef struct ne_run {
+    const ne_alias* alias;
+    const int32_t* pairs_dev;
+    int64_t n_pairs;
+    uint64_t sample_base;
+    int32_t* neg_out_dev;
+} ne_run;
+ne_status ne_train_runs(ne_tables* tables, const ne_run* runs_host, int64_t n_runs, int64_t B, int32_t K,
+                        const float* lr_host, void* hip_stream);
 
 /*
  * ne_train_block on samples that stay in pinned host memory (the paper's training pipeline, Sec. IV-A:

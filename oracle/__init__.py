@@ -23,7 +23,7 @@ def build(force: bool = True) -> str:
     """Compile the oracle with gcc.  No fast-math, no FMA contraction: plain IEEE fp64."""
     if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fast-math",
-               "-Wall", "-Wextra", "-o", _SO, _SRC, "-lm"]
+               "-Wall", "-Wextra", "-pthread", "-o", _SO, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _SO
 
@@ -56,6 +56,9 @@ def _bind(lib):
     lib.oracle_train_batch.argtypes = [p, p, c.c_int64, c.c_int32, p, c.c_int64, c.c_int32,
                                        c.c_float, p]
     lib.oracle_train_batch.restype = c.c_int
+    lib.oracle_train_batch_threads.argtypes = [p, p, c.c_int64, c.c_int32, p, c.c_int64, c.c_int32,
+                                               c.c_float, p, c.c_int32]
+    lib.oracle_train_batch_threads.restype = c.c_int
     lib.oracle_train_batch_shared.argtypes = [p, p, c.c_int64, c.c_int32, p, c.c_int64, p, c.c_int32, c.c_float,
                                               c.c_float, c.c_int32, c.POINTER(c.c_double)]
     lib.oracle_train_batch_shared.restype = c.c_int
@@ -148,6 +151,23 @@ def train_batch(X: np.ndarray, C: np.ndarray, pairs: np.ndarray, neg: np.ndarray
                                     _ptr(neg))
     if rc != 0:
         raise ValueError(f"oracle_train_batch failed ({rc})")
+
+
+def train_batch_threads(X: np.ndarray, C: np.ndarray, pairs: np.ndarray, neg: np.ndarray, lr: float,
+                        threads: int) -> None:
+    """train_batch with the pairs shared out over host threads (per-thread fp64 sums added in thread order);
+    exists for timing the oracle on all cores."""
+    _chk(X, np.float32, "X")
+    _chk(C, np.float32, "C")
+    _chk(pairs, np.int32, "pairs")
+    _chk(neg, np.int32, "neg")
+    V, d = X.shape
+    B = pairs.shape[0]
+    assert C.shape == X.shape and pairs.shape == (B, 2) and neg.ndim == 2 and neg.shape[0] == B
+    rc = _load().oracle_train_batch_threads(_ptr(X), _ptr(C), V, d, _ptr(pairs), B, neg.shape[1], np.float32(lr),
+                                            _ptr(neg), int(threads))
+    if rc != 0:
+        raise ValueError(f"oracle_train_batch_threads failed ({rc})")
 
 
 def eval_loss(X: np.ndarray, C: np.ndarray, pairs: np.ndarray, neg: np.ndarray) -> float:

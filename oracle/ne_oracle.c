@@ -23,17 +23,21 @@
  * and the sums are applied once.
  *
  * Arithmetic is fp64 everywhere; tables are stored as fp32.
- * No blocking, no threads, no reordering: loops are in the order of the maths.
+ * No blocking, no reordering: loops are in the order of the maths.  No threads either,
+ * but for oracle_train_batch_threads, the same step shared out over host threads
+ * so that the oracle can be timed on all cores of a machine.
  *
  * Pins (tests/, -m "not gpu"): finite differences and torch-CPU autograd for the
  * update, closed forms for the loss and for the first batch from a zero context
  * table, exact integer identity + 10^7-draw frequencies for the alias table,
  * rocRAND's host-callable Philox engine and big-integer arithmetic for Philox,
  * hand values and the loss function's positive term for the pair score,
- * a worked example, the sample count of full walks and a brute-force set for the walk samples.
+ * a worked example, the sample count of full walks and a brute-force set for the walk samples;
+ * oracle_train_batch_threads against the pinned oracle_train_batch.
  * Parity unpinned: none of the functions below.
  */
 #include <math.h>
+#include <pthread.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -204,7 +208,7 @@ static int dm_init(delta_map* m, int64_t V, int64_t cap, int32_t d)
 {
     m->slot_of = (int64_t*)malloc((size_t)V * sizeof(int64_t));
     m->rows = (int64_t*)malloc((size_t)(cap > 0 ? cap : 1) * sizeof(int64_t));
-    m->acc = (double*)calloc((size_t)(cap > 0 ? cap : 1) * (size_t)d, sizeof(double));
+    m->acc = (double*)malloc((size_t)(cap > 0 ? cap : 1) * (size_t)d * sizeof(double));   /* a row is zeroed when first touched */
     m->count = 0; m->cap = cap; m->d = d;
     if (!m->slot_of || !m->rows || !m->acc) return -1;
     for (int64_t i = 0; i < V; ++i) m->slot_of[i] = -1;
@@ -212,7 +216,11 @@ static int dm_init(delta_map* m, int64_t V, int64_t cap, int32_t d)
 }
 static double* dm_row(delta_map* m, int64_t row)
 {
-    if (m->slot_of[row] < 0) { m->slot_of[row] = m->count; m->rows[m->count] = row; m->count++; }
+    if (m->slot_of[row] < 0) {
+        m->slot_of[row] = m->count; m->rows[m->count] = row;
+        memset(m->acc + m->count * (int64_t)m->d, 0, (size_t)m->d * sizeof(double));
+        m->count++;
+    }
     return m->acc + m->slot_of[row] * (int64_t)m->d;
 }
 static void dm_free(delta_map* m) { free(m->slot_of); free(m->rows); free(m->acc); }
@@ -266,6 +274,162 @@ int oracle_train_batch(float* X, float* C, int64_t V, int32_t d, const int32_t* 
     }
     dm_free(&DX); dm_free(&DC);
     return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* The same step with the pairs spread over host threads, for timing the       */
+/* oracle on all cores of a machine next to the one-thread figure.  Thread t   */
+/* takes the t-th contiguous share of the pairs and accumulates, exactly as    */
+/* above, into delta maps of its own; then every thread adds up, in the order  */
+/* of the threads, all threads' sums for the rows it owns (row % threads) and  */
+/* applies them.  Only the order of the fp64 sums differs from                 */
+/* oracle_train_batch (pinned to it in tests/).                                */
+/* Returns 0, -1 on a bad id, -2 no memory, -3 thread creation failed.         */
+/* ------------------------------------------------------------------------- */
+typedef struct share_job {
+    float* X; float* C; int32_t d; const int32_t* pairs; int32_t K; double lr; const int32_t* neg;
+    int64_t b0, b1;                 /* this thread's share of the pairs                          */
+    delta_map DX, DC;               /* its own sums over that share                              */
+    delta_map GX, GC;               /* totals of the rows it owns (row % T == its index)         */
+    struct share_job* all; int64_t T, self;
+} share_job;
+
+/* Phase 1: the loop of oracle_train_batch over this thread's share of the pairs. */
+static void* share_accumulate(void* arg)
+{
+    share_job* jb = (share_job*)arg;
+    const int32_t d = jb->d, K = jb->K;
+    for (int64_t b = jb->b0; b < jb->b1; ++b) {
+        const int64_t src = jb->pairs[2 * b];
+        const float* x = jb->X + src * (int64_t)d;
+        double* dx = dm_row(&jb->DX, src);
+        for (int32_t j = 0; j <= K; ++j) {
+            const int64_t id = (j == 0) ? jb->pairs[2 * b + 1] : jb->neg[b * K + (j - 1)];
+            const float* c = jb->C + id * (int64_t)d;
+            double s = 0.0;
+            for (int32_t i = 0; i < d; ++i) s += (double)x[i] * (double)c[i];
+            const double g = (j == 0) ? 1.0 - sigmoid(s) : -sigmoid(s);
+            double* dc = dm_row(&jb->DC, id);
+            for (int32_t i = 0; i < d; ++i) {
+                dx[i] += jb->lr * g * (double)c[i];
+                dc[i] += jb->lr * g * (double)x[i];
+            }
+        }
+    }
+    return NULL;
+}
+
+/* Phase 2: this thread adds up, in the order of the threads, every thread's sums for the rows it   */
+/* owns, and applies the totals to the tables (one rounding to fp32 per element).                  */
+static void* share_merge(void* arg)
+{
+    share_job* me = (share_job*)arg;
+    const int32_t d = me->d;
+    for (int64_t t = 0; t < me->T; ++t) {
+        const share_job* src = &me->all[t];
+        for (int64_t r = 0; r < src->DX.count; ++r) {
+            if (src->DX.rows[r] % me->T != me->self) continue;
+            double* g = dm_row(&me->GX, src->DX.rows[r]);
+            for (int32_t i = 0; i < d; ++i) g[i] += src->DX.acc[r * (int64_t)d + i];
+        }
+        for (int64_t r = 0; r < src->DC.count; ++r) {
+            if (src->DC.rows[r] % me->T != me->self) continue;
+            double* g = dm_row(&me->GC, src->DC.rows[r]);
+            for (int32_t i = 0; i < d; ++i) g[i] += src->DC.acc[r * (int64_t)d + i];
+        }
+    }
+    for (int64_t t = 0; t < me->GX.count; ++t) {
+        float* row = me->X + me->GX.rows[t] * (int64_t)d;
+        for (int32_t i = 0; i < d; ++i) row[i] = (float)((double)row[i] + me->GX.acc[t * (int64_t)d + i]);
+    }
+    for (int64_t t = 0; t < me->GC.count; ++t) {
+        float* row = me->C + me->GC.rows[t] * (int64_t)d;
+        for (int32_t i = 0; i < d; ++i) row[i] = (float)((double)row[i] + me->GC.acc[t * (int64_t)d + i]);
+    }
+    return NULL;
+}
+
+static int run_on_threads(share_job* jobs, pthread_t* tid, int64_t T, void* (*fn)(void*))
+{
+    int64_t started = 0;
+    int rc = 0;
+    for (int64_t t = 0; t < T; ++t, ++started)
+        if (pthread_create(&tid[t], NULL, fn, &jobs[t]) != 0) { rc = -3; break; }
+    for (int64_t t = 0; t < started; ++t) pthread_join(tid[t], NULL);
+    return rc;
+}
+
+/* Memory of thread t's four delta maps, kept from one call to the next (fresh pages cost more than   */
+/* the arithmetic when every call maps and unmaps a few hundred MB per thread).  slot_of is all -1    */
+/* between calls: a call resets the entries it has set.                                               */
+enum { MAX_SHARE_THREADS = 256 };
+static struct { char* base; size_t bytes; int64_t V, d, cap[4]; } share_pool[MAX_SHARE_THREADS];   /* cap: the layout it holds */
+
+static char* pool_take(char** cur, size_t bytes) { char* p = *cur; *cur += (bytes + 63) & ~(size_t)63; return p; }
+static void pool_map(delta_map* m, char** cur, int64_t V, int64_t cap, int32_t d)
+{
+    m->slot_of = (int64_t*)pool_take(cur, (size_t)V * sizeof(int64_t));
+    m->rows = (int64_t*)pool_take(cur, (size_t)(cap > 0 ? cap : 1) * sizeof(int64_t));
+    m->acc = (double*)pool_take(cur, (size_t)(cap > 0 ? cap : 1) * (size_t)d * sizeof(double));
+    m->count = 0; m->cap = cap; m->d = d;
+}
+static void pool_reset(delta_map* m) { for (int64_t r = 0; r < m->count; ++r) m->slot_of[m->rows[r]] = -1; }
+
+int oracle_train_batch_threads(float* X, float* C, int64_t V, int32_t d, const int32_t* pairs, int64_t B,
+                               int32_t K, float lr_f, const int32_t* neg, int32_t threads)
+{
+    for (int64_t b = 0; b < B; ++b) {
+        if (pairs[2 * b] < 0 || pairs[2 * b] >= V || pairs[2 * b + 1] < 0 || pairs[2 * b + 1] >= V) return -1;
+        for (int32_t k = 0; k < K; ++k)
+            if (neg[b * K + k] < 0 || neg[b * K + k] >= V) return -1;
+    }
+    int64_t T = threads < 1 ? 1 : (threads > MAX_SHARE_THREADS ? MAX_SHARE_THREADS : threads);
+    if (T > B) T = B > 0 ? B : 1;
+    share_job* jobs = (share_job*)calloc((size_t)T, sizeof(share_job));
+    pthread_t* tid = (pthread_t*)calloc((size_t)T, sizeof(pthread_t));
+    int rc = 0;
+    if (!jobs || !tid) { free(jobs); free(tid); return -2; }
+    for (int64_t t = 0; t < T && rc == 0; ++t) {
+        share_job* jb = &jobs[t];
+        jb->X = X; jb->C = C; jb->d = d; jb->pairs = pairs; jb->K = K; jb->lr = (double)lr_f; jb->neg = neg;
+        jb->b0 = B * t / T; jb->b1 = B * (t + 1) / T;
+        jb->all = jobs; jb->T = T; jb->self = t;
+        const int64_t n = jb->b1 - jb->b0;
+        /* a thread owns at most min(rows named, its share of V) rows */
+        const int64_t own = (V + T - 1) / T;
+        const int64_t cap[4] = { n, n * (int64_t)(K + 1), B < own ? B : own,
+                                 B * (int64_t)(K + 1) < own ? B * (int64_t)(K + 1) : own };
+        size_t need = 0;
+        for (int i = 0; i < 4; ++i)
+            need += (((size_t)V * 8 + 63) & ~(size_t)63) + (((size_t)(cap[i] > 0 ? cap[i] : 1) * 8 + 63) & ~(size_t)63) +
+                    (((size_t)(cap[i] > 0 ? cap[i] : 1) * (size_t)d * 8 + 63) & ~(size_t)63);
+        /* same layout as the last call: the slot_of arrays are where they were, all -1 */
+        int fresh = share_pool[t].V != V || share_pool[t].d != d;
+        for (int i = 0; i < 4; ++i) fresh = fresh || share_pool[t].cap[i] != cap[i];
+        if (share_pool[t].bytes < need) {
+            free(share_pool[t].base);
+            share_pool[t].base = (char*)malloc(need);
+            share_pool[t].bytes = share_pool[t].base ? need : 0;
+            fresh = 1;
+            if (!share_pool[t].base) { share_pool[t].V = 0; rc = -2; break; }
+        }
+        share_pool[t].V = V; share_pool[t].d = d;
+        for (int i = 0; i < 4; ++i) share_pool[t].cap[i] = cap[i];
+        char* cur = share_pool[t].base;
+        delta_map* maps[4] = { &jb->DX, &jb->DC, &jb->GX, &jb->GC };
+        for (int i = 0; i < 4; ++i) {
+            pool_map(maps[i], &cur, V, cap[i], d);
+            if (fresh) for (int64_t r = 0; r < V; ++r) maps[i]->slot_of[r] = -1;
+        }
+    }
+    if (rc == 0) rc = run_on_threads(jobs, tid, T, share_accumulate);
+    if (rc == 0) rc = run_on_threads(jobs, tid, T, share_merge);
+    for (int64_t t = 0; t < T; ++t)
+        if (share_pool[t].base && jobs[t].DX.slot_of) {
+            pool_reset(&jobs[t].DX); pool_reset(&jobs[t].DC); pool_reset(&jobs[t].GX); pool_reset(&jobs[t].GC);
+        }
+    free(jobs); free(tid);
+    return rc;
 }
 
 /* Loss of a batch at the current tables, summed over pairs (not averaged):    */

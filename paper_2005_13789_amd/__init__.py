@@ -25,12 +25,18 @@ NE_MAX_NEGATIVES = 62
 NE_MAX_BATCH = 1 << 22
 
 EXPORTS = (
-    "ne_create_tables", "ne_build_neg_alias", "ne_workspace_bytes", "ne_train_batch", "ne_train_block", "ne_train_block_pinned", "ne_train_walks",
+    "ne_create_tables", "ne_build_neg_alias", "ne_workspace_bytes", "ne_train_batch", "ne_train_block", "ne_train_runs", "ne_train_block_pinned", "ne_train_walks",
     "ne_shared_workspace_bytes", "ne_train_batch_shared", "ne_train_batch_shared_static", "ne_train_batch_async", "ne_set_vertex_window", "ne_eval_loss",
     "ne_score_pairs", "ne_set_tuning", "ne_validate_pairs", "ne_hash_position", "ne_profile_enable", "ne_profile_read", "ne_destroy_tables", "ne_destroy_alias", "ne_last_error",
 )
 
 _lib = None
+
+
+class NeRun(ctypes.Structure):
+    """struct ne_run of include/ne.h."""
+    _fields_ = [("alias", ctypes.c_void_p), ("pairs_dev", ctypes.c_void_p), ("n_pairs", ctypes.c_int64),
+                ("sample_base", ctypes.c_uint64), ("neg_out_dev", ctypes.c_void_p)]
 
 
 class NeError(RuntimeError):
@@ -61,6 +67,8 @@ def lib() -> ctypes.CDLL:
     L.ne_train_batch.restype = c.c_int
     L.ne_train_block.argtypes = [vp, vp, vp, c.c_int64, c.c_int64, c.c_int32, c.POINTER(c.c_float), c.c_uint64, vp, vp]
     L.ne_train_block.restype = c.c_int
+    L.ne_train_runs.argtypes = [vp, c.POINTER(NeRun), c.c_int64, c.c_int64, c.c_int32, c.POINTER(c.c_float), vp]
+    L.ne_train_runs.restype = c.c_int
     L.ne_train_block_pinned.argtypes = [vp, vp, vp, c.c_int64, c.c_int64, c.c_int32, c.POINTER(c.c_float), c.c_uint64, vp,
                                         vp, vp]
     L.ne_train_block_pinned.restype = c.c_int
@@ -220,6 +228,26 @@ def ne_train_block(tables: Tables, alias: Alias | None, pairs: torch.Tensor, B: 
         raise TypeError("neg_out needs n_pairs*K int32 elements")
     _check(lib().ne_train_block(tables.handle, alias.handle if alias else None, pp, n_pairs, B, K, arr, sample_base,
                                 np_, _stream_ptr(stream)))
+
+
+def ne_train_runs(tables: Tables, runs, B: int, K: int, lrs, stream=None) -> None:
+    """runs: sequence of (alias, pairs int32 [n][2] CUDA, sample_base) or (alias, pairs, sample_base, neg_out);
+    lrs: one float per batch, the runs' batches in order."""
+    arr = (NeRun * max(len(runs), 1))()
+    n_batches = 0
+    for i, run in enumerate(runs):
+        alias, pairs, sample_base = run[0], run[1], run[2]
+        neg_out = run[3] if len(run) > 3 else None
+        n = int(pairs.shape[0])
+        if neg_out is not None and neg_out.numel() < n * K:
+            raise TypeError("neg_out needs n_pairs*K int32 elements")
+        arr[i] = NeRun(alias.handle if alias else None, _dev_ptr(pairs, torch.int32, "pairs") or None, n, sample_base,
+                       _dev_ptr(neg_out, torch.int32, "neg_out") or None)
+        n_batches += -(-n // B) if B > 0 else 0
+    if len(lrs) < n_batches:
+        raise TypeError("lrs needs one learning rate per batch")
+    lr_arr = (ctypes.c_float * max(n_batches, 1))(*[float(v) for v in lrs[:n_batches]])
+    _check(lib().ne_train_runs(tables.handle, arr, len(runs), B, K, lr_arr, _stream_ptr(stream)))
 
 
 def ne_train_block_pinned(tables: Tables, alias: Alias | None, pairs_host: torch.Tensor, B: int, K: int, lrs,

@@ -1419,6 +1419,19 @@ hipError_t launch_fill(uint32_t* p, size_t n, uint32_t v, hipStream_t st)
     return hipGetLastError();
 }
 
+// The state every batch expects to find: hash positions empty, flags, delta slots and arrival counters zero.
+hipError_t clear_workspace(const Workspace& w, int32_t dim, hipStream_t st)
+{
+    hipError_t e = hipSuccess;
+    for (int i = 0; i < 2 && e == hipSuccess; ++i) {
+        e = launch_fill(reinterpret_cast<uint32_t*>(w.prep[i].slots), static_cast<size_t>(w.cap) * 2, 0xFFFFFFFFu, st);
+        if (e == hipSuccess) e = launch_fill(reinterpret_cast<uint32_t*>(w.prep[i].shared), w.cap / 4, 0u, st);
+    }
+    if (e == hipSuccess) e = launch_fill(reinterpret_cast<uint32_t*>(w.delta), static_cast<size_t>(w.cap) * dim, 0u, st);
+    if (e == hipSuccess) e = launch_fill(w.count, w.cap, 0u, st);
+    return e;
+}
+
 ne_status check_batch_args(const ne_tables* t, const ne_alias* al, const int32_t* pairs, int64_t B, int32_t K,
                            Shape* shape)
 {
@@ -1443,6 +1456,15 @@ ne_status run_batches(ne_tables* t, int64_t n_batches, int64_t R, int32_t window
                              hipStream_t st, PrepFn prep, TrainFn train)
 {
     const Workspace& w = t->ws;
+    // A launch that failed part-way through an earlier run left hash positions, flags or slots in use:
+    // start from a clean workspace again (the tables may hold a partly applied batch; that is the caller's
+    // to judge from the error it got then).
+    if (t->workspace_dirty) {
+        const hipError_t ce = clear_workspace(w, t->dim, st);
+        if (ce != hipSuccess) return fail(NE_ERR_HIP, std::string("workspace re-clear launch: ") + hipGetErrorString(ce));
+        t->workspace_dirty = false;
+    }
+    t->workspace_dirty = true;   // until the last launch of this run has been enqueued
     PrepArgs cur = prep(0);
     cur.fetch_blocks = 0;   // a prefetch only rides in train launches
     const unsigned grid0 = prep_blocks(cur.refs);
@@ -1497,6 +1519,7 @@ ne_status run_batches(ne_tables* t, int64_t n_batches, int64_t R, int32_t window
         t->batches_done += 1;
         cur = next;
     }
+    t->workspace_dirty = false;
     return NE_OK;
 }
 
@@ -1533,7 +1556,7 @@ ne_status ne_create_tables(ne_tables** out, int64_t num_nodes, int32_t dim, floa
     ne_tables* t = new (std::nothrow) ne_tables{};
     if (!t) return fail(NE_ERR_NOMEM, "host allocation failed");
     t->num_nodes = num_nodes; t->dim = dim; t->vertex = vertex_dev; t->context = context_dev; t->seed = seed;
-    t->max_batch = 0; t->max_negatives = 0; t->batches_done = 0; t->profile_every = 0; t->ev_used = 0;
+    t->max_batch = 0; t->max_negatives = 0; t->batches_done = 0; t->workspace_dirty = false; t->profile_every = 0; t->ev_used = 0;
     t->tune_list_cap = -1; t->tune_sweep = 0;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
 
@@ -1548,13 +1571,7 @@ ne_status ne_create_tables(ne_tables** out, int64_t num_nodes, int32_t dim, floa
             return fail(NE_ERR_ARG, "workspace_dev is NULL, not 256-byte aligned, or smaller than ne_workspace_bytes()");
         }
         t->ws = w; t->max_batch = max_batch; t->max_negatives = max_negatives;
-        hipError_t e = hipSuccess;
-        for (int i = 0; i < 2 && e == hipSuccess; ++i) {
-            e = launch_fill(reinterpret_cast<uint32_t*>(w.prep[i].slots), static_cast<size_t>(w.cap) * 2, 0xFFFFFFFFu, st);
-            if (e == hipSuccess) e = launch_fill(reinterpret_cast<uint32_t*>(w.prep[i].shared), w.cap / 4, 0u, st);
-        }
-        if (e == hipSuccess) e = launch_fill(reinterpret_cast<uint32_t*>(w.delta), static_cast<size_t>(w.cap) * dim, 0u, st);
-        if (e == hipSuccess) e = launch_fill(w.count, w.cap, 0u, st);
+        const hipError_t e = clear_workspace(w, dim, st);
         if (e != hipSuccess) {
             delete t;
             return fail(NE_ERR_HIP, std::string("workspace init launch: ") + hipGetErrorString(e));
@@ -1691,20 +1708,37 @@ ne_status ne_build_neg_alias(ne_alias** out, const uint32_t* degree_host, int64_
     return NE_OK;
 }
 
-// pairs_dev: the samples on the device; or, with staging != nullptr, the device address of the samples in
-// pinned host memory, which are then prefetched batch by batch into the ring staging[3][B].
-static ne_status train_block_impl(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t n_pairs, int64_t B,
-                                  int32_t K, const float* lr_host, uint64_t sample_base, int32_t* neg_out_dev,
-                                  int2* staging, void* hip_stream)
+// The batches of a sequence of runs (each run: one sample block with its negative-sampling table), B pairs
+// each but for the last of a run.  With staging != nullptr (one run only) pairs_dev is the device address of
+// samples in pinned host memory, which are prefetched batch by batch into the ring staging[3][B].
+static ne_status train_runs_impl(ne_tables* t, const ne_run* runs, int64_t n_runs, int64_t B, int32_t K,
+                                 const float* lr_host, int2* staging, void* hip_stream)
 {
+    if (!t) return fail(NE_ERR_ARG, "tables handle is NULL");
+    if (n_runs < 0 || n_runs > (static_cast<int64_t>(1) << 24)) return fail(NE_ERR_ARG, "n_runs out of range");
+    if (n_runs > 0 && !runs) return fail(NE_ERR_ARG, "runs_host is NULL");
     Shape shape;
-    ne_status rc = check_batch_args(t, al, pairs_dev, B, K, &shape);
-    if (rc != NE_OK) return rc;
-    if (n_pairs < 0 || n_pairs > (static_cast<int64_t>(1) << 40)) return fail(NE_ERR_ARG, "n_pairs out of range");
-    if (n_pairs == 0) return NE_OK;
-    if (B < 1) return fail(NE_ERR_ARG, "B must be at least 1");
+    struct Batch { int64_t run, first, count; };
+    std::vector<Batch> batches;
+    for (int64_t r = 0; r < n_runs; ++r) {
+        const ne_run& run = runs[r];
+        if (run.n_pairs < 0 || run.n_pairs > (static_cast<int64_t>(1) << 40)) return fail(NE_ERR_ARG, "n_pairs out of range");
+        // (an empty run may come without a pairs pointer)
+        const ne_status rc = check_batch_args(t, run.alias, run.pairs_dev, run.n_pairs > 0 ? B : (B < 0 ? B : 0), K, &shape);
+        if (rc != NE_OK) return rc;
+        if (run.n_pairs == 0) continue;
+        if (B < 1) return fail(NE_ERR_ARG, "B must be at least 1");
+        if (!run.pairs_dev) return fail(NE_ERR_ARG, "pairs_dev is NULL");
+        try {
+            for (int64_t first = 0; first < run.n_pairs; first += B)
+                batches.push_back({r, first, run.n_pairs - first < B ? run.n_pairs - first : B});
+        } catch (const std::bad_alloc&) {
+            return fail(NE_ERR_NOMEM, "host allocation failed");
+        }
+    }
+    const int64_t n_batches = static_cast<int64_t>(batches.size());
+    if (n_batches == 0) return NE_OK;
     if (!lr_host) return fail(NE_ERR_ARG, "lr_host is NULL");
-    const int64_t n_batches = (n_pairs + B - 1) / B;
     for (int64_t i = 0; i < n_batches; ++i)
         if (!std::isfinite(lr_host[i])) return fail(NE_ERR_ARG, "lr is not finite");
     if (t->max_batch <= 0) return fail(NE_ERR_STATE, "tables were created without a training workspace");
@@ -1718,34 +1752,33 @@ static ne_status train_block_impl(ne_tables* t, const ne_alias* al, const int32_
     auto prep_args = [&](int64_t i) {
         PrepArgs pa{};
         if (i >= n_batches) return pa;   // refs = 0: nothing to prepare
-        const int64_t first = i * B;
-        const int64_t Bi = (n_pairs - first < B) ? n_pairs - first : B;
+        const Batch& bt = batches[i];
+        const ne_run& run = runs[bt.run];
+        const ne_alias* al = run.alias;
         const PrepSlot& ps = w.prep[i & 1];
-        pa.pairs = staging ? staging + (i % 3) * B : reinterpret_cast<const int2*>(pairs_dev) + first;
+        pa.pairs = staging ? staging + (i % 3) * B : reinterpret_cast<const int2*>(run.pairs_dev) + bt.first;
         if (staging && i + 1 < n_batches) {
             // the launch that trains batch i - 1 and claims batch i also fetches batch i + 1
-            const int64_t f = (i + 1) * B;
-            pa.fetch_src = reinterpret_cast<const int2*>(pairs_dev) + f;
+            pa.fetch_src = reinterpret_cast<const int2*>(run.pairs_dev) + batches[i + 1].first;
             pa.fetch_dst = staging + ((i + 1) % 3) * B;
-            pa.fetch_n = (n_pairs - f < B) ? n_pairs - f : B;
+            pa.fetch_n = batches[i + 1].count;
             pa.fetch_blocks = kFetchBlocks;
         }
-        pa.refs = static_cast<uint32_t>(Bi * R); pa.R = static_cast<uint32_t>(R); pa.xrefs = 1; pa.K = K;
-        pa.sample_base = sample_base + static_cast<uint64_t>(first);
+        pa.refs = static_cast<uint32_t>(bt.count * R); pa.R = static_cast<uint32_t>(R); pa.xrefs = 1; pa.K = K;
+        pa.sample_base = run.sample_base + static_cast<uint64_t>(bt.first);
         pa.k0 = static_cast<uint32_t>(t->seed); pa.k1 = static_cast<uint32_t>(t->seed >> 32);
         pa.alias = al ? al->table : nullptr; pa.alias_n = al ? static_cast<uint64_t>(al->n) : 1; pa.alias_base = al ? al->base : 0;
         uint32_t positions = kSweepPerBlock;     // hash positions this batch uses
-        while (positions < kHashFactor * static_cast<uint32_t>(Bi * R)) positions <<= 1;
+        while (positions < kHashFactor * static_cast<uint32_t>(bt.count * R)) positions <<= 1;
         pa.slots = ps.slots; pa.mask = positions - 1; pa.shared = ps.shared; pa.ids = ps.ids; pa.posbuf = ps.posbuf;
-        pa.neg_out = neg_out_dev ? neg_out_dev + first * K : nullptr;
+        pa.neg_out = run.neg_out_dev ? run.neg_out_dev + bt.first * K : nullptr;
         return pa;
     };
 
     if (staging) {   // batches 0 and 1 have no launch to ride along with
         for (int64_t i = 0; i < 2 && i < n_batches; ++i) {
-            const int64_t f = i * B, cnt = (n_pairs - f < B) ? n_pairs - f : B;
             hipLaunchKernelGGL(fetch_pairs_kernel, dim3(kFetchBlocks), dim3(256), 0, st,
-                               reinterpret_cast<const int2*>(pairs_dev) + f, staging + (i % 3) * B, cnt);
+                               reinterpret_cast<const int2*>(runs[0].pairs_dev) + batches[i].first, staging + (i % 3) * B, batches[i].count);
             hipError_t fe = hipGetLastError();
             if (fe != hipSuccess) return fail(NE_ERR_HIP, std::string("fetch launch: ") + hipGetErrorString(fe));
         }
@@ -1754,11 +1787,18 @@ static ne_status train_block_impl(ne_tables* t, const ne_alias* al, const int32_
                        [&](const TrainArgs& ta, const PrepArgs& next) { return launch_train(shape, ta, next, st); });
 }
 
+ne_status ne_train_runs(ne_tables* t, const ne_run* runs_host, int64_t n_runs, int64_t B, int32_t K,
+                        const float* lr_host, void* hip_stream)
+{
+    return train_runs_impl(t, runs_host, n_runs, B, K, lr_host, nullptr, hip_stream);
+}
+
 ne_status ne_train_block(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t n_pairs, int64_t B,
                          int32_t K, const float* lr_host, uint64_t sample_base, int32_t* neg_out_dev,
                          void* hip_stream)
 {
-    return train_block_impl(t, al, pairs_dev, n_pairs, B, K, lr_host, sample_base, neg_out_dev, nullptr, hip_stream);
+    const ne_run run{al, pairs_dev, n_pairs, sample_base, neg_out_dev};
+    return train_runs_impl(t, &run, 1, B, K, lr_host, nullptr, hip_stream);
 }
 
 ne_status ne_train_block_pinned(ne_tables* t, const ne_alias* al, const int32_t* pairs_host_pinned, int64_t n_pairs,
@@ -1777,8 +1817,8 @@ ne_status ne_train_block_pinned(ne_tables* t, const ne_alias* al, const int32_t*
             return fail(NE_ERR_ARG, std::string("pairs_host_pinned is not pinned (page-locked) host memory: ") + hipGetErrorString(e));
         }
     }
-    return train_block_impl(t, al, static_cast<const int32_t*>(src_dev), n_pairs, B, K, lr_host, sample_base, neg_out_dev,
-                            reinterpret_cast<int2*>(staging_dev), hip_stream);
+    const ne_run run{al, static_cast<const int32_t*>(src_dev), n_pairs, sample_base, neg_out_dev};
+    return train_runs_impl(t, &run, 1, B, K, lr_host, reinterpret_cast<int2*>(staging_dev), hip_stream);
 }
 
 ne_status ne_train_walks(ne_tables* t, const ne_alias* al, const int32_t* walks_dev, int64_t n_walks,

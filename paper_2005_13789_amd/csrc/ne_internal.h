@@ -58,6 +58,7 @@ struct ne_tables {
     int32_t max_negatives;
     Workspace ws;
     uint64_t batches_done;
+    bool workspace_dirty;    // a launch failed in the middle of a run of batches: hash state, flags and slots may be half-used
     int32_t tune_list_cap;   // ne_set_tuning: -1 = automatic
     int32_t tune_sweep;      // ne_set_tuning: 0 = automatic
     // optional timing of the train kernel with HIP events (ne_profile_enable / ne_profile_read)

@@ -34,6 +34,12 @@ class SubpartTrainer:
     def run(self, alias, pairs_by_subpart, B: int, K: int, lrs_by_subpart, sample_bases):
         """pairs_by_subpart[s]: CUDA int32 [n_s][2] whose sources all lie in sub-part s (absolute ids)."""
         k = self.k
+        # Everything the caller has enqueued on its current stream (workspace clearing and table init of
+        # ne_create_tables, the pair tensors, the context table) must be done before the private streams
+        # start; and the caller's stream must see the result afterwards.
+        cur = torch.cuda.current_stream()
+        for st in (self.s_in, self.s_train, self.s_out):
+            st.wait_stream(cur)
         loaded = [torch.cuda.Event() for _ in range(k)]
         trained = [torch.cuda.Event() for _ in range(k)]
         stored = [torch.cuda.Event() for _ in range(k)]
@@ -58,5 +64,7 @@ class SubpartTrainer:
             with torch.cuda.stream(self.s_out):
                 self.host[lo:hi].copy_(buf, non_blocking=True)
             stored[s].record(self.s_out)
-        for ev in stored:
+        cur.wait_stream(self.s_train)      # the context table's updates
+        cur.wait_stream(self.s_out)        # the vertex rows' way back to the host
+        for ev in stored:                  # the host copy is complete when run() returns
             ev.synchronize()

@@ -69,6 +69,16 @@ def test_host_side_argument_errors():
     assert L.ne_train_block(tables, None, fake, 10, 8, 0, None, 0, None, None) == ne.NE_ERR_ARG     # no lr
     assert L.ne_train_block(tables, None, fake, 10, 8, 0, lr, 0, None, None) == ne.NE_ERR_STATE     # no workspace
     assert L.ne_train_block(tables, None, fake, 0, 8, 0, lr, 0, None, None) == ne.NE_OK             # nothing to do
+    # runs: (tables, runs, n_runs, B, K, lr, stream)
+    one = (ne.NeRun * 1)(ne.NeRun(None, fake.value, 10, 0, None))
+    assert L.ne_train_runs(None, one, 1, 8, 0, lr, None) == ne.NE_ERR_ARG
+    assert L.ne_train_runs(tables, None, 1, 8, 0, lr, None) == ne.NE_ERR_ARG
+    assert L.ne_train_runs(tables, one, -1, 8, 0, lr, None) == ne.NE_ERR_ARG
+    assert L.ne_train_runs(tables, one, 1, 0, 0, lr, None) == ne.NE_ERR_ARG             # B = 0
+    assert L.ne_train_runs(tables, one, 1, 8, 0, None, None) == ne.NE_ERR_ARG           # no lr
+    assert L.ne_train_runs(tables, one, 1, 8, 3, lr, None) == ne.NE_ERR_ARG             # K > 0, no alias
+    assert L.ne_train_runs(tables, one, 1, 8, 0, lr, None) == ne.NE_ERR_STATE           # no workspace
+    assert L.ne_train_runs(tables, one, 0, 8, 0, lr, None) == ne.NE_OK                  # nothing to do
     assert L.ne_eval_loss(tables, None, fake, 1, 0, 0, None, None, None) == ne.NE_ERR_ARG
     assert L.ne_eval_loss(tables, None, fake, 0, 0, 0, fake, None, None) == ne.NE_OK            # B = 0
     assert L.ne_build_neg_alias(ctypes.byref(out), None, 4, 0, fake, None) == ne.NE_ERR_ARG
@@ -102,7 +112,7 @@ def test_host_side_argument_errors():
     assert L.ne_train_block_pinned(tables, None, None, 10, 8, 0, lr, 0, fake, None, None) == ne.NE_ERR_ARG
     assert b"pairs_host_pinned" in L.ne_last_error()
     assert L.ne_train_block_pinned(None, None, None, 0, 8, 0, lr, 0, fake, None, None) == ne.NE_ERR_ARG
-    assert L.ne_train_block_pinned(tables, None, None, 0, 8, 0, lr, 0, None, None, None) == ne.NE_ERR_ARG   # as ne_train_block: pairs NULL
+    assert L.ne_train_block_pinned(tables, None, None, 0, 8, 0, lr, 0, None, None, None) == ne.NE_OK        # no pairs: nothing to do
     # scores: (tables, pairs, n, second_from_context, scores, stream)
     assert L.ne_score_pairs(None, fake, 1, 1, fake, None) == ne.NE_ERR_ARG
     assert L.ne_score_pairs(tables, fake, -1, 1, fake, None) == ne.NE_ERR_ARG

@@ -8,6 +8,7 @@ has closed forms for hand-made tables, and the first batch from a zero context t
 import math
 
 import numpy as np
+import pytest
 import torch
 
 import oracle
@@ -203,3 +204,27 @@ def test_init_tables():
     X2, _ = oracle.init_tables(50, 100, seed=1)
     assert X2.min() > -0.5 / 100 and X2.max() < 0.5 / 100
     assert not np.array_equal(X2[:, :100], oracle.init_tables(50, 100, seed=2)[0])
+
+
+@pytest.mark.parametrize("threads", [1, 2, 3, 8, 100])
+def test_threaded_step_equals_the_plain_step(threads):
+    """oracle_train_batch_threads (used only to time the oracle on all cores) against the pinned plain step:
+    the same fp64 terms, summed per thread and then across threads, so the fp32 results agree to the last
+    bit except where a sum lands within 1e-16 of a rounding boundary."""
+    rng = np.random.default_rng(threads)
+    V, d, B, K = 300, 12, 257, 4
+    X = rng.normal(0, 0.4, (V, d)).astype(np.float32)
+    C = rng.normal(0, 0.4, (V, d)).astype(np.float32)
+    pairs = np.minimum((rng.pareto(0.8, (B, 2)) * 10).astype(np.int64), V - 1).astype(np.int32)   # hubs: rows repeat
+    neg = rng.integers(0, V, (B, K)).astype(np.int32)
+    X1, C1, X2, C2 = X.copy(), C.copy(), X.copy(), C.copy()
+    oracle.train_batch(X1, C1, pairs, neg, 0.05)
+    oracle.train_batch_threads(X2, C2, pairs, neg, 0.05, threads)
+    assert not np.array_equal(X1, X)
+    for a, b in ((X1, X2), (C1, C2)):
+        assert np.abs(a.astype(np.float64) - b).max() <= 1.2e-7 * np.abs(a).max()
+        assert (a.view(np.uint32) != b.view(np.uint32)).mean() < 1e-3
+    untouched = np.ones(V, bool); untouched[pairs[:, 1]] = False; untouched[neg.reshape(-1)] = False
+    assert np.array_equal(C2[untouched].view(np.uint32), C[untouched].view(np.uint32))
+    with pytest.raises(ValueError):
+        oracle.train_batch_threads(X2, C2, np.array([[0, V]], np.int32), neg[:1], 0.05, 2)
