@@ -251,15 +251,28 @@ ne_status ne_train_batch_shared_static(ne_tables* tables, const ne_alias* alias,
                                        int32_t* neg_out_dev, double* loss_sum_dev, void* hip_stream);
 
 /*
- * Per-sample ("asynchronous") training: the same arithmetic as ne_train_batch, but every pair is
- * trained on its own as in the loop of Algorithm 1, without waiting for the other pairs of the
- * call: each pair reads its 2+K rows as they are at that moment and writes all of them back at once
- * (old + delta, plain stores).  Pairs of one call run concurrently, so two pairs that name the same
- * row race: one of the two updates may be lost, and a pair may read a row that another pair of the
- * same call has already rewritten.  The result therefore depends on timing and is not reproducible
- * bit for bit; it equals ne_train_batch exactly (up to fp32 rounding) only when no row is named
- * twice in the call.  Needs no workspace.  Negatives, arguments and errors as for ne_train_batch.
+ * Per-sample ("asynchronous") training: the loop of Algorithm 1 taken pair by pair instead of batch by
+ * batch, as far as a parallel machine can.  The arithmetic per pair is that of ne_train_batch, and no
+ * update is ever lost, but the pairs of a call do not wait for each other:
+ *   - a row that only one reference of the call names is read and rewritten by that reference alone
+ *     (old + delta, plain stores), exactly as in ne_train_batch;
+ *   - a row that several references of the call name receives each of their deltas as fp32 atomic adds on
+ *     the table row itself, at the moment the reference has computed it.  Every delta arrives, so the row
+ *     ends at old + the sum of all deltas; but a pair that reads the row may see it before, after or half-way
+ *     through another pair's addition.  Gradients of such pairs are therefore evaluated at a mixture of the
+ *     values before the call and values already updated inside it, where ne_train_batch uses the values
+ *     before the call for all of them and a sequential loop the fully updated ones.
+ * The result depends on timing wherever rows are shared inside a call and is not reproducible bit for bit;
+ * it equals ne_train_batch (up to fp32 rounding) when no row is named twice in the call.  No delta slots,
+ * no second pass over the shared rows: the call costs the train kernel plus a small id-only launch per batch.
+ * ne_train_block_async takes a run of batches like ne_train_block (the id-only work of batch i+1 rides in
+ * the kernels of batch i); ne_train_batch_async is one batch.  Both need the training workspace of
+ * ne_create_tables (they find out which rows are shared the way ne_train_batch does).
+ * Negatives, arguments and errors as for ne_train_block / ne_train_batch.
  */
+ne_status ne_train_block_async(ne_tables* tables, const ne_alias* alias, const int32_t* pairs_dev,
+                               int64_t n_pairs, int64_t B, int32_t K, const float* lr_host,
+                               uint64_t sample_base, int32_t* neg_out_dev, void* hip_stream);
 ne_status ne_train_batch_async(ne_tables* tables, const ne_alias* alias, const int32_t* pairs_dev,
                                int64_t B, int32_t K, float lr, uint64_t sample_base,
                                int32_t* neg_out_dev, void* hip_stream);

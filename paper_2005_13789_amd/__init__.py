@@ -26,7 +26,7 @@ NE_MAX_BATCH = 1 << 22
 
 EXPORTS = (
     "ne_create_tables", "ne_build_neg_alias", "ne_workspace_bytes", "ne_train_batch", "ne_train_block", "ne_train_runs", "ne_train_block_pinned", "ne_train_walks",
-    "ne_shared_workspace_bytes", "ne_train_batch_shared", "ne_train_batch_shared_static", "ne_train_batch_async", "ne_set_vertex_window", "ne_eval_loss",
+    "ne_shared_workspace_bytes", "ne_train_batch_shared", "ne_train_batch_shared_static", "ne_train_batch_async", "ne_train_block_async", "ne_set_vertex_window", "ne_eval_loss",
     "ne_score_pairs", "ne_set_tuning", "ne_validate_pairs", "ne_hash_position", "ne_profile_enable", "ne_profile_read", "ne_destroy_tables", "ne_destroy_alias", "ne_last_error",
 )
 
@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
     L.ne_train_batch_shared_static.restype = c.c_int
     L.ne_train_batch_async.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_float, c.c_uint64, vp, vp]
     L.ne_train_batch_async.restype = c.c_int
+    L.ne_train_block_async.argtypes = [vp, vp, vp, c.c_int64, c.c_int64, c.c_int32, c.POINTER(c.c_float), c.c_uint64, vp, vp]
+    L.ne_train_block_async.restype = c.c_int
     L.ne_set_vertex_window.argtypes = [vp, vp, c.c_int64, c.c_int64]
     L.ne_set_vertex_window.restype = c.c_int
     L.ne_eval_loss.argtypes = [vp, vp, vp, c.c_int64, c.c_int32, c.c_uint64, vp, vp, vp]
@@ -290,13 +292,30 @@ def ne_train_walks(tables: Tables, alias: Alias | None, walks: torch.Tensor, wal
 
 def ne_train_batch_async(tables: Tables, alias: Alias | None, pairs: torch.Tensor, K: int, lr: float,
                          sample_base: int, neg_out: torch.Tensor | None = None, stream=None) -> None:
-    """Unsynchronised per-sample step on pairs int32 [B][2] (CUDA): rows named twice race."""
+    """Per-sample step on pairs int32 [B][2] (CUDA): no update is lost, but pairs that share a row do not wait
+    for each other (shared rows take atomic adds on the table while other pairs may still read them)."""
     B = int(pairs.shape[0])
     pp = _dev_ptr(pairs, torch.int32, "pairs")
     np_ = _dev_ptr(neg_out, torch.int32, "neg_out")
     if neg_out is not None and neg_out.numel() < B * K:
         raise TypeError("neg_out needs B*K int32 elements")
     _check(lib().ne_train_batch_async(tables.handle, alias.handle if alias else None, pp, B, K, lr, sample_base,
+                                      np_, _stream_ptr(stream)))
+
+
+def ne_train_block_async(tables: Tables, alias: Alias | None, pairs: torch.Tensor, B: int, K: int, lrs,
+                         sample_base: int, neg_out: torch.Tensor | None = None, stream=None) -> None:
+    """ne_train_batch_async on all of pairs int32 [n_pairs][2] (CUDA) in consecutive batches of B; lrs: one float per batch."""
+    n_pairs = int(pairs.shape[0])
+    n_batches = -(-n_pairs // B) if B > 0 else 0
+    if len(lrs) < n_batches:
+        raise TypeError("lrs needs one learning rate per batch")
+    arr = (ctypes.c_float * max(n_batches, 1))(*[float(v) for v in lrs[:n_batches]])
+    pp = _dev_ptr(pairs, torch.int32, "pairs")
+    np_ = _dev_ptr(neg_out, torch.int32, "neg_out")
+    if neg_out is not None and neg_out.numel() < n_pairs * K:
+        raise TypeError("neg_out needs n_pairs*K int32 elements")
+    _check(lib().ne_train_block_async(tables.handle, alias.handle if alias else None, pp, n_pairs, B, K, arr, sample_base,
                                       np_, _stream_ptr(stream)))
 
 

@@ -35,8 +35,10 @@
 // The same four phases serve three shapes of batch: pairs (ne_train_batch, ne_train_block), and walks
 // (ne_train_walks: on-device augmentation) by entries or by segments, which differ only in how the
 // references are laid out (claim) and in what a lane group or workgroup keeps on chip (train).
-// Beside the exact step: an unsynchronised per-sample kernel (ne_train_batch_async), the loss and
-// pair-score kernels for evaluation, and table initialisation.
+// Beside the exact step: the per-sample mode (ne_train_block_async: the same launches, but a shared
+// row's deltas are added to the table row itself with atomics while other pairs may still read it, and
+// the apply phase has no row work), the loss and pair-score kernels for evaluation, and table
+// initialisation.
 #include "ne_internal.h"
 
 static thread_local std::string g_last_error;
@@ -444,6 +446,9 @@ struct TrainArgs {
     uint32_t* count;      // [positions] references of the row that have arrived (zero between batches)
     uint32_t* members;    // [positions][kListCap] reference indices of the first arrivals
     float4* dbuf;         // [references][d4] their deltas
+    // per-sample mode (ne_train_block_async): a shared row's deltas go straight to the table row with atomics
+    // instead of to a slot, so pairs that read the row later see them; nothing is left for the apply phase
+    int32_t direct;
 };
 
 // Longest member list of a shared row.
@@ -482,7 +487,7 @@ __device__ __forceinline__ void to_consecutive(const float4 (&v)[NCH], float (&o
 // retire one dword per memory channel clock and would otherwise bound batches with many shared rows.
 template <int G, int NCH>
 __device__ __forceinline__ void shared_row_delta(const TrainArgs& a, uint32_t pos, uint32_t ref, uint32_t rank,
-                                                 const float4 (&dv)[NCH], float* lds_row, int lg, int d4)
+                                                 const float4 (&dv)[NCH], float* lds_row, int lg, int d4, float4* row)
 {
     if (rank < a.list_cap) {
         float4* out = a.dbuf + static_cast<int64_t>(ref) * d4;
@@ -495,7 +500,7 @@ __device__ __forceinline__ void shared_row_delta(const TrainArgs& a, uint32_t po
     } else {
         float t[4 * NCH];
         to_consecutive<G, NCH>(dv, t, lds_row, lg);
-        float* slot = a.delta + static_cast<int64_t>(pos) * (d4 * 4);
+        float* slot = a.direct ? reinterpret_cast<float*>(row) : a.delta + static_cast<int64_t>(pos) * (d4 * 4);
 #pragma unroll
         for (int m = 0; m < 4 * NCH; ++m) {
             const int e = lg + m * G;
@@ -568,7 +573,7 @@ __device__ __forceinline__ void context_rows_of_pair(const TrainArgs& a, int K, 
                     }
                     if (lg == 0) a.members[static_cast<int64_t>(pos) * kListCap + rank] = ref;
                 } else {
-                    float* slot = a.delta + static_cast<int64_t>(pos) * d;
+                    float* slot = a.direct ? reinterpret_cast<float*>(crow[jj]) : a.delta + static_cast<int64_t>(pos) * d;
 #pragma unroll
                     for (int m = 0; m < 4 * NCH; ++m) {
                         const int e = lg + m * G;
@@ -652,7 +657,7 @@ __global__ __launch_bounds__(kTrainThreads) void train_kernel(TrainArgs a, PrepA
                 xrow[ci] = make_float4(xr[i].x + dx[i].x, xr[i].y + dx[i].y, xr[i].z + dx[i].z, xr[i].w + dx[i].w);
         }
     } else {
-        shared_row_delta<G, NCH>(a, pos0, static_cast<uint32_t>(b * R), rank0, dx, lds[grp], lg, d4);
+        shared_row_delta<G, NCH>(a, pos0, static_cast<uint32_t>(b * R), rank0, dx, lds[grp], lg, d4, xrow);
     }
 }
 
@@ -732,7 +737,7 @@ __global__ __launch_bounds__(kTrainThreads) void train_walk_kernel(TrainArgs a, 
                 xrow[ci] = make_float4(xr[i].x + dx[i].x, xr[i].y + dx[i].y, xr[i].z + dx[i].z, xr[i].w + dx[i].w);
         }
     } else {
-        shared_row_delta<G, NCH>(a, pos0, static_cast<uint32_t>(ref0), rank0, dx, lds[grp], lg, d4);
+        shared_row_delta<G, NCH>(a, pos0, static_cast<uint32_t>(ref0), rank0, dx, lds[grp], lg, d4, xrow);
     }
 }
 
@@ -863,7 +868,7 @@ __global__ __launch_bounds__(kTrainThreads) void train_seg_kernel(TrainArgs a, P
                     xrow[ci] = make_float4(xr[i].x + dx[i].x, xr[i].y + dx[i].y, xr[i].z + dx[i].z, xr[i].w + dx[i].w);
             }
         } else {
-            shared_row_delta<G, NCH>(a, pos_x, static_cast<uint32_t>(ref0 + grp), rank_x, dx, scratch + grp * ROW, lg, d4);
+            shared_row_delta<G, NCH>(a, pos_x, static_cast<uint32_t>(ref0 + grp), rank_x, dx, scratch + grp * ROW, lg, d4, xrow);
         }
     }
 
@@ -906,7 +911,8 @@ __global__ __launch_bounds__(kTrainThreads) void train_seg_kernel(TrainArgs a, P
                     crow[ci] = make_float4(cr[i].x + dc[i].x, cr[i].y + dc[i].y, cr[i].z + dc[i].z, cr[i].w + dc[i].w);
             }
         } else {
-            shared_row_delta<G, NCH>(a, pos_c, static_cast<uint32_t>(ref), rank_c, dc, scratch + grp * ROW, lg, d4);
+            shared_row_delta<G, NCH>(a, pos_c, static_cast<uint32_t>(ref), rank_c, dc, scratch + grp * ROW, lg, d4,
+                                     a.C + static_cast<int64_t>(id) * d4);
         }
     }
 }
@@ -940,6 +946,7 @@ struct ApplyArgs {
     uint32_t* count;
     const uint32_t* members;
     const float4* dbuf;
+    int32_t direct;       // per-sample mode: the train kernel has already added the shared rows' deltas to the tables
 };
 
 template <int kSweepPerThread, int GL, int CH>
@@ -977,7 +984,7 @@ __global__ __launch_bounds__(256) void apply_kernel(ApplyArgs a, PrepArgs next, 
         for (int i = 0; i < kSweepPerThread / 2; ++i) out[i] = empty2;
     }
     __syncthreads();
-    const int n = todo_count;
+    const int n = a.direct ? 0 : todo_count;
     const int lg = threadIdx.x & (GL - 1);
     for (int e = threadIdx.x / GL; e < n; e += 256 / GL) {
         const uint2 item = todo_list[e];
@@ -1121,101 +1128,6 @@ __global__ __launch_bounds__(256) void loss_kernel(LossArgs a)
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// async kernel (ne_train_batch_async): per-sample training without synchronisation, the loop of
-// Algorithm 1 taken literally on a parallel machine.  One lane group per pair draws the negatives,
-// gathers the rows, scores, and writes every row back at once with plain stores (old + delta).  No
-// row is protected: two pairs that name the same row race, the later store wins, and a pair may read
-// a row another pair has just rewritten.  Every row costs exactly one read and one write.
-// ---------------------------------------------------------------------------------------------
-struct AsyncArgs {
-    float4* X;
-    float4* C;
-    const int2* pairs;
-    int64_t B;
-    int32_t K;
-    int32_t d4;
-    float lr;
-    uint64_t sample_base;
-    uint32_t k0, k1;
-    const uint2* alias;
-    uint64_t alias_n;
-    int32_t alias_base;
-    int32_t* neg_out;
-};
-
-template <int G, int NCH, int JB>
-__global__ __launch_bounds__(256) void async_kernel(AsyncArgs a)
-{
-    constexpr int GROUPS = 256 / G;
-    const int lg = threadIdx.x & (G - 1);
-    const int64_t b = static_cast<int64_t>(blockIdx.x) * GROUPS + (threadIdx.x / G);
-    if (b >= a.B) return;   // whole groups leave together; groups never communicate
-    const int K = a.K;
-    const int d4 = a.d4;
-    const int2 pr = a.pairs[b];
-
-    // lane lg owns context row j = lg of the pair: j = 0 the positive, j = 1..K negative j-1
-    int32_t id_mine = pr.y;
-    if (lg >= 1 && lg <= K) {
-        id_mine = draw_negative(a.sample_base + static_cast<uint64_t>(b), static_cast<uint32_t>(lg - 1), a.k0, a.k1,
-                                a.alias, a.alias_n, a.alias_base);
-        if (a.neg_out) a.neg_out[b * K + (lg - 1)] = id_mine;
-    }
-    float4* xrow = a.X + static_cast<int64_t>(pr.x) * d4;
-    float4 xr[NCH], dx[NCH];
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-        const int ci = lg + i * G;
-        xr[i] = (ci < d4) ? xrow[ci] : make_float4(0.f, 0.f, 0.f, 0.f);
-        dx[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-    }
-    for (int j0 = 0; j0 <= K; j0 += JB) {
-        float4 cr[JB][NCH];
-        float part[JB];
-        float4* crow[JB];
-#pragma unroll
-        for (int jj = 0; jj < JB; ++jj) {
-            const int j = j0 + jj;
-            const int32_t id = __shfl(id_mine, j <= K ? j : K, G);
-            crow[jj] = a.C + static_cast<int64_t>(id) * d4;
-#pragma unroll
-            for (int i = 0; i < NCH; ++i) {
-                const int ci = lg + i * G;
-                cr[jj][i] = (j <= K && ci < d4) ? crow[jj][ci] : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-        }
-#pragma unroll
-        for (int jj = 0; jj < JB; ++jj) {
-            float p = 0.0f;
-#pragma unroll
-            for (int i = 0; i < NCH; ++i) p += dot4(xr[i], cr[jj][i]);
-            part[jj] = p;
-        }
-#pragma unroll
-        for (int jj = 0; jj < JB; ++jj) part[jj] = group_sum<G>(part[jj]);
-#pragma unroll
-        for (int jj = 0; jj < JB; ++jj) {
-            const int j = j0 + jj;
-            if (j <= K) {
-                const float sg = sigmoidf(part[jj]);
-                const float g = a.lr * (j == 0 ? 1.0f - sg : -sg);
-#pragma unroll
-                for (int i = 0; i < NCH; ++i) {
-                    const int ci = lg + i * G;
-                    dx[i] = axpy4(g, cr[jj][i], dx[i]);
-                    if (ci < d4) crow[jj][ci] = axpy4(g, xr[i], cr[jj][i]);
-                }
-            }
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-        const int ci = lg + i * G;
-        if (ci < d4) xrow[ci] = make_float4(xr[i].x + dx[i].x, xr[i].y + dx[i].y, xr[i].z + dx[i].z, xr[i].w + dx[i].w);
-    }
-}
-
 __global__ __launch_bounds__(256) void validate_pairs_kernel(const int32_t* __restrict__ ids, int64_t count,
                                                              int64_t num_nodes, unsigned long long* bad)
 {
@@ -1341,20 +1253,6 @@ hipError_t launch_loss(const Shape& s, const LossArgs& a, hipStream_t st)
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_async(const Shape& s, const AsyncArgs& a, hipStream_t st)
-{
-    const int groups = 256 / s.G;
-    const unsigned grid = static_cast<unsigned>((a.B + groups - 1) / groups);
-#define NE_CASE(G_, N_)                                                                          \
-    if (s.G == G_ && s.NCH == N_) {                                                              \
-        hipLaunchKernelGGL((async_kernel<G_, N_, 6>), dim3(grid), dim3(256), 0, st, a);          \
-        return hipGetLastError();                                                                \
-    }
-    NE_FOR_EACH_SHAPE(NE_CASE)
-#undef NE_CASE
-    return hipErrorInvalidValue;
-}
-
 // Largest batch: keeps every grid and the hash capacity inside 32 bits.
 constexpr int64_t kMaxBatch = static_cast<int64_t>(1) << 22;
 // Hash positions per reference, before rounding up to a power of two (load <= 1/2).  Four per
@@ -1453,7 +1351,7 @@ ne_status check_batch_args(const ne_tables* t, const ne_alias* al, const int32_t
 // launches the shape's train kernel.
 template <class PrepFn, class TrainFn>
 ne_status run_batches(ne_tables* t, int64_t n_batches, int64_t R, int32_t window, int32_t K, const float* lr_host,
-                             hipStream_t st, PrepFn prep, TrainFn train)
+                             hipStream_t st, PrepFn prep, TrainFn train, bool direct = false)
 {
     const Workspace& w = t->ws;
     // A launch that failed part-way through an earlier run left hash positions, flags or slots in use:
@@ -1482,7 +1380,9 @@ ne_status run_batches(ne_tables* t, int64_t n_batches, int64_t R, int32_t window
         ta.X = reinterpret_cast<float4*>(t->vertex); ta.C = reinterpret_cast<float4*>(t->context);
         ta.B = cur.refs / R; ta.window = window; ta.K = K; ta.d4 = t->dim / 4; ta.lr = lr_host[i];
         ta.ids = ps.ids; ta.posbuf = ps.posbuf; ta.shared = ps.shared; ta.delta = w.delta;
-        const BatchTuning tune = batch_tuning(t, cur.refs);
+        BatchTuning tune = batch_tuning(t, cur.refs);
+        if (direct) tune.list_cap = 0;   // no slots, no lists: shared rows take their atomics on the table itself
+        ta.direct = direct ? 1 : 0;
         ta.list_cap = tune.list_cap; ta.count = w.count; ta.members = w.members; ta.dbuf = reinterpret_cast<float4*>(w.dbuf);
         const bool timed = profile_begin(t, st);
         e = train(ta, next);
@@ -1492,7 +1392,7 @@ ne_status run_batches(ne_tables* t, int64_t n_batches, int64_t R, int32_t window
         ApplyArgs aa{};
         aa.X = ta.X; aa.C = ta.C; aa.d4 = ta.d4; aa.delta = reinterpret_cast<float4*>(w.delta);
         aa.positions = cur.mask + 1; aa.slots = ps.slots; aa.shared = ps.shared;
-        aa.list_cap = ta.list_cap; aa.count = w.count; aa.members = w.members; aa.dbuf = ta.dbuf;
+        aa.list_cap = ta.list_cap; aa.count = w.count; aa.members = w.members; aa.dbuf = ta.dbuf; aa.direct = ta.direct;
         const unsigned resolve_blocks = prep_blocks(next.refs);
         const int per_thread = tune.sweep_per_thread;
         const unsigned sweep_blocks = aa.positions / (256u * per_thread);
@@ -1712,7 +1612,7 @@ ne_status ne_build_neg_alias(ne_alias** out, const uint32_t* degree_host, int64_
 // each but for the last of a run.  With staging != nullptr (one run only) pairs_dev is the device address of
 // samples in pinned host memory, which are prefetched batch by batch into the ring staging[3][B].
 static ne_status train_runs_impl(ne_tables* t, const ne_run* runs, int64_t n_runs, int64_t B, int32_t K,
-                                 const float* lr_host, int2* staging, void* hip_stream)
+                                 const float* lr_host, int2* staging, void* hip_stream, bool direct = false)
 {
     if (!t) return fail(NE_ERR_ARG, "tables handle is NULL");
     if (n_runs < 0 || n_runs > (static_cast<int64_t>(1) << 24)) return fail(NE_ERR_ARG, "n_runs out of range");
@@ -1784,7 +1684,7 @@ static ne_status train_runs_impl(ne_tables* t, const ne_run* runs, int64_t n_run
         }
     }
     return run_batches(t, n_batches, R, 0, K, lr_host, st, prep_args,
-                       [&](const TrainArgs& ta, const PrepArgs& next) { return launch_train(shape, ta, next, st); });
+                       [&](const TrainArgs& ta, const PrepArgs& next) { return launch_train(shape, ta, next, st); }, direct);
 }
 
 ne_status ne_train_runs(ne_tables* t, const ne_run* runs_host, int64_t n_runs, int64_t B, int32_t K,
@@ -1901,28 +1801,22 @@ ne_status ne_train_batch(ne_tables* t, const ne_alias* al, const int32_t* pairs_
     return ne_train_block(t, al, pairs_dev, B, B, K, &lr, sample_base, neg_out_dev, hip_stream);
 }
 
+ne_status ne_train_block_async(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t n_pairs, int64_t B,
+                               int32_t K, const float* lr_host, uint64_t sample_base, int32_t* neg_out_dev,
+                               void* hip_stream)
+{
+    const ne_run run{al, pairs_dev, n_pairs, sample_base, neg_out_dev};
+    return train_runs_impl(t, &run, 1, B, K, lr_host, nullptr, hip_stream, true);
+}
+
 ne_status ne_train_batch_async(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t B, int32_t K,
                                float lr, uint64_t sample_base, int32_t* neg_out_dev, void* hip_stream)
 {
-    Shape shape;
-    ne_status rc = check_batch_args(t, al, pairs_dev, B, K, &shape);
-    if (rc != NE_OK) return rc;
-    if (!std::isfinite(lr)) return fail(NE_ERR_ARG, "lr is not finite");
-    if (B == 0) return NE_OK;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    AsyncArgs aa{};
-    aa.X = reinterpret_cast<float4*>(t->vertex); aa.C = reinterpret_cast<float4*>(t->context);
-    aa.pairs = reinterpret_cast<const int2*>(pairs_dev);
-    aa.B = B; aa.K = K; aa.d4 = t->dim / 4; aa.lr = lr; aa.sample_base = sample_base;
-    aa.k0 = static_cast<uint32_t>(t->seed); aa.k1 = static_cast<uint32_t>(t->seed >> 32);
-    aa.alias = al ? al->table : nullptr; aa.alias_n = al ? static_cast<uint64_t>(al->n) : 1; aa.alias_base = al ? al->base : 0;
-    aa.neg_out = neg_out_dev;
-    const bool timed = profile_begin(t, st);
-    hipError_t e = launch_async(shape, aa, st);
-    if (e != hipSuccess) return fail(NE_ERR_HIP, std::string("async launch: ") + hipGetErrorString(e));
-    if (timed) profile_end(t, st);
-    t->batches_done += 1;
-    return NE_OK;
+    if (B == 0) {
+        Shape shape;
+        return check_batch_args(t, al, pairs_dev, B, K, &shape);
+    }
+    return ne_train_block_async(t, al, pairs_dev, B, B, K, &lr, sample_base, neg_out_dev, hip_stream);
 }
 
 ne_status ne_eval_loss(const ne_tables* t, const ne_alias* al, const int32_t* pairs_dev, int64_t B, int32_t K,

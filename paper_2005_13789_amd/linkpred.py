@@ -99,8 +99,8 @@ def train(train_edges: np.ndarray, num_nodes: int, dim: int = 64, epochs: int = 
           batch: int = 4096, lr0: float = 0.025, walk_length: int = 40, window: int = 5, seed: int = 0,
           mode: str = "sync", device: str = "cuda:0"):
     """Embeddings from walks over the training edges: per epoch one walk per node, window pairs shuffled,
-    batches of `batch` pairs through ne_train_block (mode "sync", the exact step) or ne_train_batch_async
-    (mode "async"), or the walks themselves through ne_train_walks (mode "walks": the exact step on batches of
+    batches of `batch` pairs through ne_train_block (mode "sync", the exact step) or ne_train_block_async
+    (mode "async", the per-sample mode), or the walks themselves through ne_train_walks (mode "walks": the exact step on batches of
     whole walks, unshuffled), learning rate decaying linearly over the run.  Returns (Tables, Alias); the handles keep
     their device tensors alive (tables.vertex, tables.context)."""
     dev = torch.device(device)
@@ -144,8 +144,7 @@ def train(train_edges: np.ndarray, num_nodes: int, dim: int = 64, epochs: int = 
         if mode == "sync":
             ne.ne_train_block(tables, alias, p, batch, negatives, lrs, done)
         elif mode == "async":
-            for s, lr in zip(starts, lrs):
-                ne.ne_train_batch_async(tables, alias, p[s:s + batch], negatives, float(lr), done + s)
+            ne.ne_train_block_async(tables, alias, p, batch, negatives, lrs, done)
         else:
             raise ValueError("mode must be 'sync', 'async' or 'walks'")
         done += n

@@ -1,12 +1,17 @@
-"""Parity of the unsynchronised per-sample mode (ne_train_batch_async).
+"""Parity of the per-sample mode (ne_train_batch_async / ne_train_block_async).
 
-Its result depends on timing wherever two pairs of a call name the same row, so there are two checks:
-element by element on batches in which no row is named twice (there it must equal the oracle's
-minibatch step, and the sequential one, to fp32 rounding), and statistically: negatives bit-exact, and a
-loss curve that trails the sequential per-sample oracle by a bounded margin and closes in on it, each side
-evolving its own tables (a row named by several pairs of one call keeps only one of their updates, so the
-mode learns hub rows more slowly: parity for this mode is partial by construction).  With thousands of
-pairs in flight on a small table that case is only required to stay finite and not to diverge.
+Rows that one reference of a call names are updated exactly as in the minibatch step; rows that several
+references name take every delta as atomic adds on the table row while other pairs may still be reading it.
+No update is lost, but the result depends on timing wherever rows are shared, so there are three checks:
+  * element by element on calls in which no row is named twice: equal to the oracle's minibatch step (and
+    to the sequential one) to fp32 rounding;
+  * negatives bit-exact always, and conservation on heavily shared rows: with scores pinned near zero
+    (every coefficient is then +-1/2 whatever the timing) every row must receive the exact sum of its
+    deltas - one lost update would show;
+  * statistically: the loss curve against the sequential per-sample oracle at 256 and at 4096 pairs per
+    call, each side evolving its own tables.  Inside a call the mode evaluates gradients at values between
+    "before the call" and "fully updated", so its curve lies between the minibatch oracle's and the
+    sequential oracle's; the bound is on the distance to the sequential one.
 """
 import numpy as np
 import pytest
@@ -49,7 +54,6 @@ def test_async_equals_oracle_without_collisions(V, d, K, B):
         keep = np.ones(B, bool)
     # pairs that were dropped still advance the sample index: train the kept ones one call per run of kept pairs
     Xo, Co = X0.copy(), C0.copy()
-    start = 0
     idx = np.flatnonzero(keep)
     runs = np.split(idx, np.flatnonzero(np.diff(idx) != 1) + 1)
     for run in runs:
@@ -62,14 +66,59 @@ def test_async_equals_oracle_without_collisions(V, d, K, B):
     assert ex <= 1e-5 and ec <= 1e-5
 
 
-def test_async_loss_curve_small_calls():
-    """R-MAT 20 k nodes / 200 k edges, walks of 40, window 5, d=128, K=5, 400 calls of 256 pairs.  Even
-    with 256 pairs in flight a hub row is named by several pairs of a call and keeps one of their
-    updates, so the curve lags the sequential oracle (measured: up to 15 % mid-way, 4 % at the end) and
-    closes in on it; the test bounds that lag."""
-    say("async, loss curve vs sequential oracle (256 pairs per call)")
-    V, d, K, B, seed, nb = 20000, 128, 5, 256, 0, 400
-    g = wl.build_graph(V, wl.rmat_edges(V, 200000, seed=0))
+@pytest.mark.parametrize("block", [False, True])
+def test_async_loses_no_update_on_shared_rows(block):
+    """Every update must arrive, however many pairs of a call share a row.  All vertex rows hold the same vector
+    e, the context table starts at zero and lr is tiny, so every score stays below 1e-5, every coefficient is
+    1/2 (label 1) or -1/2 (label 0) to fp32 resolution, and context row r must end at
+    (lr/2) (times named as context - times drawn as negative) e  whatever the timing.  One lost update would move
+    the row by (lr/2) e; fp32 accumulation of at most 2500 terms stays below a tenth of that, so the bar is half
+    an update, in absolute terms, on every row."""
+    V, d, K, B, seed = 3000, 64, 5, 4096, 5
+    say(f"async conservation on shared rows (block={block})")
+    rng = np.random.default_rng(1)
+    deg = (rng.pareto(1.0, V) * 3).astype(np.uint32) + 1
+    e = np.linspace(0.01, 0.05, d).astype(np.float32)
+    X0 = np.tile(e, (V, 1))
+    C0 = np.zeros((V, d), np.float32)
+    m = GpuModel(V, d, seed, deg, K, B, X=X0, C=C0)
+    pairs = np.minimum((rng.pareto(0.8, (2 * B, 2)) * V / 50).astype(np.int64), rng.integers(0, V, (2 * B, 2))).astype(np.int32)
+    pd = torch.from_numpy(pairs).cuda()
+    lr = 1e-8
+    neg_dev = torch.empty((2 * B, K), dtype=torch.int32, device="cuda:0")
+    if block:
+        ne.ne_train_block_async(m.tables, m.alias, pd, B, K, [lr, lr], 11, neg_dev)
+    else:
+        for i in range(2):
+            ne.ne_train_batch_async(m.tables, m.alias, pd[i * B:(i + 1) * B], K, lr, 11 + i * B, neg_dev[i * B:(i + 1) * B])
+    Xg, Cg = m.host_tables()
+    thr, al, _ = oracle.build_alias(deg)
+    neg = oracle.sample_negatives(seed, 11, 2 * B, K, thr, al)
+    assert np.array_equal(neg_dev.cpu().numpy(), neg)
+    as_ctx = np.bincount(pairs[:, 1], minlength=V)
+    as_neg = np.bincount(neg.reshape(-1), minlength=V)
+    named = as_ctx + as_neg
+    say(f"  context rows are named up to {named.max()} times in the two calls; {(named > 1).sum()} rows more than once")
+    assert 500 < named.max() < 2500
+    want = 0.5 * np.float32(lr) * (as_ctx - as_neg).astype(np.float64)[:, None] * e.astype(np.float64)[None, :]
+    update = 0.5 * lr * float(e.max())
+    worst = np.abs(Cg.astype(np.float64) - want).max() / update
+    say(f"  largest deviation from the exact sums: {worst:.3f} of one update")
+    assert worst < 0.5
+    assert np.array_equal(Xg, X0)                 # dx = lr * sum g_j c_j is far below fp32 resolution of x here
+
+
+@pytest.mark.parametrize("B,nb,lr,every", [(256, 400, 0.2, 40), (4096, 100, 0.025, 10)])
+def test_async_loss_curve_against_sequential_oracle(B, nb, lr, every):
+    """256 pairs per call on R-MAT 20 k nodes, and config 1's shape (10 k nodes, 4096 pairs per call, lr 0.025):
+    the loss on a fixed probe set, GPU per-sample mode against the sequential per-sample oracle, each side evolving
+    its own tables.  Stated bound: within 4 % of the sequential oracle's loss at every probe, within 2.5 % at the end
+    (measured 0.9 % / 0.4 % at 256 pairs per call and 2.7 % / 1.5 % at 4096: gradients inside a call are taken at
+    values between those before the call and the fully updated ones, and the gap grows with the call)."""
+    config1 = B == 4096
+    V, d, K, seed = (10000 if config1 else 20000), 128, 5, 0
+    say(f"async, loss curve vs sequential oracle ({B} pairs per call, {nb} calls)")
+    g = wl.build_graph(V, wl.rmat_edges(V, 10 * V, seed=0))
     pairs_all = wl.walk_pairs(g, 40, 5, nb * B, seed=0)
     deg = g.degree.numpy().astype(np.uint32)
     m = GpuModel(V, d, seed, deg, K, B)
@@ -83,7 +132,7 @@ def test_async_loss_curve_small_calls():
         s = t * B
         pd, pn = pd_all[s:s + B], np.ascontiguousarray(pn_all[s:s + B])
         neg_o = oracle.sample_negatives(seed, s, B, K, thr, alias)
-        if t % 40 == 0 or t == nb - 1:
+        if t % every == 0 or t == nb - 1:
             m.loss.zero_()
             ne.ne_eval_loss(m.tables, m.alias, probe_d, K, 10**9, m.loss)
             lg = m.loss.item() / 4096
@@ -92,34 +141,23 @@ def test_async_loss_curve_small_calls():
             final_gap = abs(lg - ls) / ls
             first = first if first is not None else ls
             last = ls
-            assert lg >= ls - 0.02 * ls       # never ahead of the lossless sequential run by more than noise
-            say(f"  call {t}: loss gpu-async {lg:.4f} sequential {ls:.4f}")
-        ne.ne_train_batch_async(m.tables, m.alias, pd, K, 0.2, s, m.neg_out)
+            say(f"  call {t}: loss gpu per-sample {lg:.4f} sequential oracle {ls:.4f}")
+        ne.ne_train_batch_async(m.tables, m.alias, pd, K, lr, s, m.neg_out)
         assert np.array_equal(m.neg_out[:B, :K].cpu().numpy(), neg_o)
-        oracle.train_sequential(Xs, Cs, pn, neg_o, 0.2)
-    say(f"  largest relative gap to the sequential oracle: {worst:.3%}")
+        oracle.train_sequential(Xs, Cs, pn, neg_o, lr)
+    say(f"  largest relative gap to the sequential oracle: {worst:.3%}, at the end {final_gap:.3%}")
     assert last < 0.97 * first          # the comparison is on a curve that actually moves
-    assert worst <= 0.20 and final_gap <= 0.08
-
-
-def test_async_under_contention_is_lossy_but_finite():
-    """Config 1 with 4096 pairs in flight on a 10 k-row table: most rows are named by many pairs of a
-    call and all but one of their updates are lost, so training is slower than the oracles; the mode
-    must stay finite, keep the negatives exact and never increase the loss above its start."""
-    say("async under contention (config 1, 4096 pairs per call)")
-    V, d, K, B, seed, nb = 10000, 128, 5, 4096, 0, 30
-    g = wl.build_graph(V, wl.rmat_edges(V, 100000, seed=0))
-    pairs_all = wl.walk_pairs(g, 40, 5, nb * B, seed=0)
-    deg = g.degree.numpy().astype(np.uint32)
-    m = GpuModel(V, d, seed, deg, K, B)
-    thr, alias, _ = oracle.build_alias(deg)
-    pd_all = pairs_all.cuda()
-    start = m.loss_sum(pd_all[:B], 0) / B
-    for t in range(nb):
-        s = t * B
-        ne.ne_train_batch_async(m.tables, m.alias, pd_all[s:s + B], K, 0.025, s, m.neg_out)
-        assert np.array_equal(m.neg_out[:B, :K].cpu().numpy(), oracle.sample_negatives(seed, s, B, K, thr, alias))
-    end = m.loss_sum(pd_all[:B], 0) / B
-    say(f"  loss {start:.4f} -> {end:.4f}")
+    assert worst <= 0.04 and final_gap <= 0.025
     Xg, Cg = m.host_tables()
-    assert np.isfinite(Xg).all() and np.isfinite(Cg).all() and end <= start + 1e-6
+    assert np.isfinite(Xg).all() and np.isfinite(Cg).all()
+
+
+def test_async_needs_the_training_workspace():
+    V, d = 200, 16
+    vertex = torch.zeros((V, d), dtype=torch.float32, device="cuda:0")
+    context = torch.zeros((V, d), dtype=torch.float32, device="cuda:0")
+    t = ne.ne_create_tables(vertex, context, 0, init=False)          # evaluate-only handle
+    pairs = torch.zeros((8, 2), dtype=torch.int32, device="cuda:0")
+    with pytest.raises(ne.NeError):
+        ne.ne_train_batch_async(t, None, pairs, 0, 0.1, 0)
+    ne.ne_train_batch_async(t, None, pairs[:0], 0, 0.1, 0)            # empty batch: no-op
