@@ -237,7 +237,7 @@ ne_status ne_train_batch_shared(ne_tables* tables, const ne_alias* alias, const 
  * library's code is loaded on that GPU until the process ends; its address is looked up on the first
  * call on each device.  The call allocates and frees nothing.
  *   Limit: ne_shared_workspace_bytes(dim, B, N) <= NE_SHARED_STATIC_SCRATCH_BYTES (for example dim 256
- *   with B <= 2048 and N <= 512, or dim 128 with B <= 4096 and N <= 1024); larger shapes return
+ *   with B <= 3072 and N <= 1024, or dim 128 with B <= 6144 and N <= 1024); larger shapes return
  *   NE_ERR_ARG and a message that names both sizes.
  *   All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two
  *   host threads) race and give wrong results; order them on one stream.  Nothing in the array has to

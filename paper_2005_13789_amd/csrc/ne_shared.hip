@@ -10,20 +10,21 @@
 // with Xq, Cq the gathered rows rounded to bf16 and fp32 accumulation on the matrix cores
 // (v_mfma_f32_32x32x16_bf16).  The positive pair of every sample is handled in full fp32.
 //
-// Four kernels per batch:
-//   stage   gathers and rounds the rows, draws the N negatives, does the positive pairs in fp32 and
-//           stages their deltas; the tables are only read.
-//   scores  one workgroup per 128 pairs and share of the negatives: S tile by tile on MFMA, sigmoid
-//           in registers, G to LDS (and transposed to memory for the dC product), dX accumulated on
-//           MFMA over the share.
+// Four kernels per batch; the tables are only read by the first two and only written by the last:
+//   prep    draws the N negatives, gathers their rows, rounds them and stores them twice in the order
+//           in which the matrix-core operands of the two products want them (one coalesced 1 KB read per
+//           operand fragment later); claims every row reference of the batch (plain-store hashing).
+//   scores  one workgroup per 32 pairs, all N negatives: gathers its pairs' rows, does the positive
+//           pairs in fp32, S block by block on MFMA with the negatives' fragments streamed from
+//           memory (they stay in L2), sigmoid in registers, G to LDS (and transposed to memory for the
+//           dC product), dX accumulated on MFMA over all negatives: a workgroup ends with the complete
+//           deltas of its pairs' source rows, no partial sums.  The resolve pass rides along.
 //   dctx    dC = G^T . Xq on MFMA, split over the batch dimension into partial sums.
 //   update  adds every staged delta to the tables.  Nothing reads the tables any more at that point,
-//           so duplicates simply add up: rows named once in the batch (found with the plain-store
-//           claim of the stage kernel and the resolve pass that rides in the scores kernel) are
-//           rewritten with plain stores, the others take fp32 atomics.
+//           so duplicates simply add up: rows named once in the batch are rewritten with plain stores,
+//           the others take fp32 atomics.
 #include <hip/hip_bf16.h>
 
-#include <atomic>
 #include <mutex>
 
 #include "ne_internal.h"
@@ -40,12 +41,11 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kRowTile = 128;    // pairs per workgroup in the scores kernel
-constexpr int kScoreThreads = 512;  // 8 wavefronts: two per SIMD, so that one's LDS traffic overlaps the other's MFMAs
-constexpr int kNegChunk = 64;    // negatives per LDS chunk in the scores kernel
-constexpr int kSplit = 16;       // partial sums of the dC product
-constexpr int kNegSplit = 4;     // at most this many workgroups per row tile in the scores kernel, each taking a share of the negatives
-constexpr int kBatchPad = 1024;  // the padded batch is a multiple of this (kSplit shares of whole 64-pair steps)
+constexpr int kPairTile = 32;      // pairs per workgroup in the scores kernel
+constexpr int kScoreThreads = 512; // 8 wavefronts: one 32-negative block of S each, one 32-column block of dX each
+constexpr int kNegChunk = 256;     // negatives per pass of the scores kernel (8 wavefronts x 32)
+constexpr int kSplit = 16;         // partial sums of the dC product
+constexpr int kBatchPad = 1024;    // the padded batch is a multiple of this (kSplit shares of whole 64-pair steps)
 
 __device__ __forceinline__ uint16_t to_bf16(float x)
 {
@@ -59,15 +59,22 @@ __device__ __forceinline__ float fast_sigmoidf(float z) { return __frcp_rn(1.0f 
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
+// Workgroup barrier for data exchanged through LDS only: waits for this wavefront's LDS operations, not for its
+// global loads and stores.  (__syncthreads also drains those, which would undo every operand fetch issued ahead of
+// its use and expose the latency of every store.)
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// MFMA 32x32x16 operand layout (checked on hardware): lane l supplies row (A) / column (B) l%32 and the 8
+// consecutive contraction indices (l/32)*8..+7 of the step; accumulator element i is row
+// (i/4)*8 + (l/32)*4 + i%4, column l%32.  A "fragment" below is what the 64 lanes of a wavefront supply
+// for one step: 64 x 8 bf16 = 1 KB, stored lane after lane.
 struct SharedWs {
-    uint16_t* Xq;    // [Bp][d]   bf16 source rows (zero beyond B)
-    uint16_t* XqT;   // [d][Bp]
-    uint16_t* Cq;    // [N][d]    bf16 negative rows
-    uint16_t* CqT;   // [d][N]
+    uint16_t* XqT;   // [d][Bp]   bf16 source rows, transposed (zero beyond B): operand of the dC product
+    uint16_t* CqP;   // [N/32][d/16][64][8]  bf16 negative rows as B fragments of S: block of 32 negatives, step over d
+    uint16_t* CqTP;  // [d/32][N/16][64][8]  the same rows as B fragments of dX: block of 32 columns, step over negatives
     uint16_t* GT;    // [N][Bp]   bf16 coefficients, transposed
-    float* dxp;      // [Bp][d]   lr * g0 * c_ctx          (positive pair, source side)
-    float* uctx;     // [Bp][d]   lr * g0 * x              (positive pair, context side)
-    float* dXn;      // [kNegSplit][Bp][d]   partial sums of G . Cq
+    float* dxs;      // [Bp][d]   complete delta of pair b's source row: lr * (g0 * c_ctx + (G . Cq)_b)
+    float* dcs;      // [Bp][d]   lr * g0 * x: delta of pair b's context row
     float* dCp;      // [kSplit][N][d] partial sums of G^T . Xq
     int32_t* negids; // [N]
     unsigned long long* slots;   // [hash_mask + 1]  (key << 32 | reference) of the reference that claimed a position last
@@ -93,14 +100,12 @@ bool shared_layout(int32_t dim, int64_t B, int32_t N, char* base, SharedWs* w)
     auto take = [&](size_t bytes) { char* p = base + off; off = up(off + bytes); return p; };
     const size_t d = static_cast<size_t>(dim), n = static_cast<size_t>(N);
     w->Bp = static_cast<int64_t>(Bp);
-    w->Xq = reinterpret_cast<uint16_t*>(take(Bp * d * 2));
     w->XqT = reinterpret_cast<uint16_t*>(take(Bp * d * 2));
-    w->Cq = reinterpret_cast<uint16_t*>(take(n * d * 2));
-    w->CqT = reinterpret_cast<uint16_t*>(take(n * d * 2));
+    w->CqP = reinterpret_cast<uint16_t*>(take(n * d * 2));
+    w->CqTP = reinterpret_cast<uint16_t*>(take(n * d * 2));
     w->GT = reinterpret_cast<uint16_t*>(take(n * Bp * 2));
-    w->dxp = reinterpret_cast<float*>(take(Bp * d * 4));
-    w->uctx = reinterpret_cast<float*>(take(Bp * d * 4));
-    w->dXn = reinterpret_cast<float*>(take(static_cast<size_t>(kNegSplit) * Bp * d * 4));
+    w->dxs = reinterpret_cast<float*>(take(Bp * d * 4));
+    w->dcs = reinterpret_cast<float*>(take(Bp * d * 4));
     w->dCp = reinterpret_cast<float*>(take(static_cast<size_t>(kSplit) * n * d * 4));
     w->negids = reinterpret_cast<int32_t*>(take(n * 4));
     size_t cap = 4096;
@@ -113,16 +118,16 @@ bool shared_layout(int32_t dim, int64_t B, int32_t N, char* base, SharedWs* w)
 }
 
 // ---------------------------------------------------------------------------------------------
-// stage kernel.  One lane group of G = D/8 lanes per row: groups [0, Bp) are the pairs, groups
-// [Bp, Bp+N) the negatives.  Lane lg holds the float4 chunks lg and lg+G of its row.
+// prep kernel.  Threads [0, N * G), in lane groups of G = D/8: negative j of the batch: draw its id, claim
+// its row, gather the row, round it, store its 8-element pieces at their places in the two fragment
+// orders.  Threads [0, 2B): claim reference t of the pairs.  All threads: clear 16 of the
+// "named more than once" flags.
 // ---------------------------------------------------------------------------------------------
-struct StageArgs {
-    const float4* X;
+struct PrepNegArgs {
     const float4* C;
     const int2* pairs;
-    int64_t B, Bp;
+    int64_t B;
     int32_t N;
-    float lr;
     uint64_t batch_index;
     uint32_t k0, k1;
     const uint2* alias;
@@ -130,138 +135,116 @@ struct StageArgs {
     int32_t alias_base;
     SharedWs w;
     int32_t* neg_out;
-    double* loss;
 };
 
+__device__ __forceinline__ uint32_t pack2(float a, float b) { return to_bf16(a) | (static_cast<uint32_t>(to_bf16(b)) << 16); }
+
 template <int D>
-__global__ __launch_bounds__(256) void stage_kernel(StageArgs a)
+__global__ __launch_bounds__(256) void prep_kernel(PrepNegArgs a)
 {
     constexpr int G = D / 8;
-    constexpr int GROUPS = 256 / G;
-    constexpr int D4 = D / 4;
-    const int lg = threadIdx.x & (G - 1);
-    const int64_t gidx = static_cast<int64_t>(blockIdx.x) * GROUPS + threadIdx.x / G;
-    float loss_term = 0.0f;
-    // the "named more than once" flags start from zero in every batch (16 per thread; the grid has
-    // more than (2 Bp + N) * 8 threads and the flag array 4..8 times (2 Bp + N) bytes)
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    // the flags start from zero in every batch
     {
-        const size_t i = (static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x) * 16;
+        const size_t i = static_cast<size_t>(t) * 16;
         if (i <= a.w.hash_mask) *reinterpret_cast<uint4*>(a.w.multi + i) = make_uint4(0u, 0u, 0u, 0u);
     }
-    if (gidx < a.Bp) {
-        const int64_t b = gidx;
-        uint2* xq = reinterpret_cast<uint2*>(a.w.Xq + b * D);
-        if (b < a.B) {
-            const int2 pr = a.pairs[b];
-            // claim: whichever reference stores last owns the position of its row's key
-            if (lg < 2) {
-                const uint32_t key = lg == 0 ? static_cast<uint32_t>(pr.x) : (static_cast<uint32_t>(pr.y) | kContextKey);
-                a.w.slots[ref_hash(key, a.w.hash_mask)] = ref_entry(key, static_cast<uint32_t>(2 * b + lg));
-            }
-            const float4* xrow = a.X + static_cast<int64_t>(pr.x) * D4;
-            const float4* crow = a.C + static_cast<int64_t>(pr.y) * D4;
-            float4 x[2], c[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) { x[i] = xrow[lg + i * G]; c[i] = crow[lg + i * G]; }
-            const float s0 = group_sum<G>(dot4(x[0], c[0]) + dot4(x[1], c[1]));
-            const float g0 = a.lr * (1.0f - sigmoidf(s0));
-            if (lg == 0) loss_term = softplusf(-s0);
-            float4* dxp = reinterpret_cast<float4*>(a.w.dxp + b * D);
-            float4* uctx = reinterpret_cast<float4*>(a.w.uctx + b * D);
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int ci = lg + i * G;
-                dxp[ci] = make_float4(g0 * c[i].x, g0 * c[i].y, g0 * c[i].z, g0 * c[i].w);
-                uctx[ci] = make_float4(g0 * x[i].x, g0 * x[i].y, g0 * x[i].z, g0 * x[i].w);
-                xq[ci] = make_uint2(to_bf16(x[i].x) | (static_cast<uint32_t>(to_bf16(x[i].y)) << 16),
-                                    to_bf16(x[i].z) | (static_cast<uint32_t>(to_bf16(x[i].w)) << 16));
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < 2; ++i) xq[lg + i * G] = make_uint2(0u, 0u);   // padding rows score zero
-        }
-    } else if (gidx < a.Bp + a.N) {
-        const int32_t j = static_cast<int32_t>(gidx - a.Bp);
-        const uint4 r = philox4x32_10(make_uint4(static_cast<uint32_t>(a.batch_index), static_cast<uint32_t>(a.batch_index >> 32),
-                                                 static_cast<uint32_t>(j), kStreamSharedNegative), a.k0, a.k1);
-        const int32_t id = a.alias_base + alias_draw(r, a.alias, a.alias_n);
-        if (lg == 0) {
-            a.w.negids[j] = id;
-            if (a.neg_out) a.neg_out[j] = id;
-            const uint32_t key = static_cast<uint32_t>(id) | kContextKey;
-            a.w.slots[ref_hash(key, a.w.hash_mask)] = ref_entry(key, static_cast<uint32_t>(2 * a.B + j));
-        }
-        const float4* crow = a.C + static_cast<int64_t>(id) * D4;
-        uint2* cq = reinterpret_cast<uint2*>(a.w.Cq + static_cast<int64_t>(j) * D);
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int ci = lg + i * G;
-            const float4 c = crow[ci];
-            const uint16_t h0 = to_bf16(c.x), h1 = to_bf16(c.y), h2 = to_bf16(c.z), h3 = to_bf16(c.w);
-            cq[ci] = make_uint2(h0 | (static_cast<uint32_t>(h1) << 16), h2 | (static_cast<uint32_t>(h3) << 16));
-            uint16_t* ct = a.w.CqT + static_cast<int64_t>(4 * ci) * a.N + j;
-            ct[0] = h0; ct[a.N] = h1; ct[2 * static_cast<int64_t>(a.N)] = h2; ct[3 * static_cast<int64_t>(a.N)] = h3;
-        }
+    // claim: whichever reference stores last owns the position of its row's key
+    if (t < 2 * a.B) {
+        const int2 pr = a.pairs[t >> 1];
+        const uint32_t key = (t & 1) ? (static_cast<uint32_t>(pr.y) | kContextKey) : static_cast<uint32_t>(pr.x);
+        a.w.slots[ref_hash(key, a.w.hash_mask)] = ref_entry(key, static_cast<uint32_t>(t));
     }
-    if (a.loss) {   // uniform over the grid
-        __shared__ double sh[4];
-        float l = loss_term;
-        for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off, 64);
-        if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = static_cast<double>(l);
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            const double t = sh[0] + sh[1] + sh[2] + sh[3];
-            if (t != 0.0) atomicAdd(a.loss, t);
+    const int64_t j64 = t / G;
+    if (j64 >= a.N) return;
+    const int j = static_cast<int>(j64), lg = static_cast<int>(t - j64 * G);
+    const uint4 r = philox4x32_10(make_uint4(static_cast<uint32_t>(a.batch_index), static_cast<uint32_t>(a.batch_index >> 32),
+                                             static_cast<uint32_t>(j), kStreamSharedNegative), a.k0, a.k1);
+    const int32_t id = a.alias_base + alias_draw(r, a.alias, a.alias_n);
+    if (lg == 0) {
+        a.w.negids[j] = id;
+        if (a.neg_out) a.neg_out[j] = id;
+        const uint32_t key = static_cast<uint32_t>(id) | kContextKey;
+        a.w.slots[ref_hash(key, a.w.hash_mask)] = ref_entry(key, static_cast<uint32_t>(2 * a.B + j));
+    }
+    // elements 8 lg .. 8 lg + 7 of the row
+    const float4* crow = a.C + static_cast<int64_t>(id) * (D / 4);
+    const float4 c0 = crow[2 * lg], c1 = crow[2 * lg + 1];
+    const uint4 piece = make_uint4(pack2(c0.x, c0.y), pack2(c0.z, c0.w), pack2(c1.x, c1.y), pack2(c1.z, c1.w));
+    // S fragments: block j / 32, step over d = lg / 2, lane = j % 32 + 32 * (lg % 2): the piece is the lane's 16 bytes
+    {
+        const size_t lane = static_cast<size_t>(j & 31) + 32u * (lg & 1);
+        const size_t frag = static_cast<size_t>(j >> 5) * (D / 16) + (lg >> 1);
+        *reinterpret_cast<uint4*>(a.w.CqP + (frag * 64 + lane) * 8) = piece;
+    }
+    // dX fragments: column c = 8 lg + e: block c / 32, step over negatives = j / 16, lane = c % 32 + 32 * ((j % 16) / 8),
+    // element j % 8 of the lane's 8
+    {
+        const uint16_t h[8] = {static_cast<uint16_t>(piece.x), static_cast<uint16_t>(piece.x >> 16), static_cast<uint16_t>(piece.y),
+                               static_cast<uint16_t>(piece.y >> 16), static_cast<uint16_t>(piece.z), static_cast<uint16_t>(piece.z >> 16),
+                               static_cast<uint16_t>(piece.w), static_cast<uint16_t>(piece.w >> 16)};
+        const size_t steps = static_cast<size_t>(a.N) / 16;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int c = 8 * lg + e;
+            const size_t lane = static_cast<size_t>(c & 31) + 32u * ((j >> 3) & 1);
+            const size_t frag = static_cast<size_t>(c >> 5) * steps + (j >> 4);
+            a.w.CqTP[(frag * 64 + lane) * 8 + (j & 7)] = h[e];
         }
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// scores kernel: one workgroup (8 wavefronts) per 128 pairs and share of the negatives.
-//   wavefront w: row quarter rh = w & 3 (32 pairs); column half ch = w >> 2
-//   S tile   : pairs rh*32.. x negatives ch*32.. of the current 64-negative chunk   (1 MFMA tile)
-//   dX tiles : pairs rh*32.. x columns ch*D/2 .. ch*D/2 + D/2                        (D/64 tiles)
-// MFMA 32x32x16 operand layout (checked on hardware): lane l supplies row/column l%32 and the 8
-// consecutive k values (l/32)*8..+7; accumulator element i is row (i/4)*8 + (l/32)*4 + i%4, column l%32.
-// LDS rows are padded by 8 bf16 so that the 16-byte fragment reads of 32 rows spread over all banks.
+// scores kernel: one workgroup (8 wavefronts) per 32 pairs, all N negatives.
+//   prologue   16 lanes per pair: gather x = vertex[src] and c = context[ctx] in fp32, positive score,
+//              g0 = lr (1 - sigma(s0)); lr g0 x goes to dcs, lr g0 c stays in registers; x rounded to bf16
+//              into LDS (and, transposed, to memory for the dC product); every wavefront then keeps the
+//              A fragments of the 32 rows (all of d) in registers.
+//   per pass of 256 negatives
+//     S      wavefront w: 32 pairs x negatives block w of the pass; B fragments straight from memory.
+//            G = -neg_scale sigma(S) as bf16 into LDS [32][256].
+//     G^T    256 negatives x 32 pairs to memory, 64 contiguous bytes per negative.
+//     dX     wavefront w: 32 pairs x columns block w (32 of d): A fragments from G in LDS, B fragments
+//            straight from memory.
+//   epilogue   dX through LDS to the pairs' lanes: dxs = lr dX + lr g0 c.
 // ---------------------------------------------------------------------------------------------
 struct ScoresArgs {
+    const float4* X;
+    const float4* C;
     SharedWs w;
     int64_t B;
     int32_t N;
+    float lr;
     float neg_scale;
     double* loss;
     const int2* pairs;
 };
 
-// Column of G inside its LDS row: the eight 16-byte groups of a row are permuted by the row's 16-row
-// block, so that the transposed read-out below (one negative, rows 16 apart) spreads over the banks
-// while a fragment read (one row, 8 consecutive negatives) stays one 16-byte access.
-__device__ __forceinline__ int g_col(int row, int col) { return ((((col >> 3) ^ (row >> 4)) & 7) << 3) | (col & 7); }
-
-template <int D>
+template <int D, bool LOSS>
 __global__ __launch_bounds__(kScoreThreads) void scores_kernel(ScoresArgs a)
 {
-    constexpr int XP = D + 8;            // pitch of Xs and Cs rows (bf16)
-    constexpr int TP = kNegChunk + 8;    // pitch of CTs and Gs rows
-    constexpr int DT = D / 64;           // dX tiles per wavefront
-    extern __shared__ uint16_t lds[];
-    uint16_t* Xs = lds;                              // [128][XP]
-    uint16_t* Cs = Xs + kRowTile * XP;               // [64][XP]
-    uint16_t* CTs = Cs + kNegChunk * XP;             // [D][TP]
-    uint16_t* Gs = CTs + D * TP;                     // [128][TP]
+    constexpr int XP = D + 8;            // pitch of the bf16 source rows in LDS (16-byte fragment reads spread over the banks)
+    constexpr int GP = kNegChunk + 8;    // pitch of G
+    constexpr int DP = D + 4;            // pitch of the fp32 dX rows
+    constexpr int KS = D / 16;           // contraction steps of S
+    constexpr int CB = D / 32;           // 32-column blocks of dX: wavefronts 0 .. CB-1 take one each
+    constexpr int NCH = D / 64;          // float4 chunks of a row per lane of a pair's 16 lanes
+    constexpr int kXsBytes = kPairTile * XP * 2, kGsBytes = kPairTile * GP * 2, kDxBytes = kPairTile * DP * 4;
+    __shared__ __align__(16) unsigned char lds_raw[(kXsBytes + kGsBytes > kDxBytes) ? kXsBytes + kGsBytes : kDxBytes];
+    uint16_t* Xs = reinterpret_cast<uint16_t*>(lds_raw);                    // [32][XP]
+    uint16_t* Gs = reinterpret_cast<uint16_t*>(lds_raw + kXsBytes);         // [32][GP]
+    float* dXs = reinterpret_cast<float*>(lds_raw);                         // [32][DP], after the last pass
     const int tid = threadIdx.x;
     const int l = tid & 63, w = tid >> 6;
-    const int rh = w & 3, ch = w >> 2;   // 32-pair quarter, half of the chunk / of the columns
-    const int64_t b0 = static_cast<int64_t>(blockIdx.x) * kRowTile;
+    const int64_t b0 = static_cast<int64_t>(blockIdx.x) * kPairTile;
     const int64_t Bp = a.w.Bp;
 
     // resolve (ids only, a by-product of this launch): a reference that finds its row's key at the
     // key's position under another reference's name flags the row as named more than once
     {
         const int64_t refs = 2 * a.B + a.N;
-        const int64_t stride = static_cast<int64_t>(gridDim.x) * gridDim.y * kScoreThreads;
-        for (int64_t r = (static_cast<int64_t>(blockIdx.y) * gridDim.x + blockIdx.x) * kScoreThreads + tid; r < refs; r += stride) {
+        const int64_t stride = static_cast<int64_t>(gridDim.x) * kScoreThreads;
+        for (int64_t r = static_cast<int64_t>(blockIdx.x) * kScoreThreads + tid; r < refs; r += stride) {
             uint32_t key;
             if (r < 2 * a.B) {
                 const int2 pr = a.pairs[r >> 1];
@@ -275,128 +258,158 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(ScoresArgs a)
         }
     }
 
-    // the source rows of this workgroup
-    for (int c = tid; c < kRowTile * (D / 8); c += kScoreThreads) {
-        const int r = c / (D / 8), q = c % (D / 8);
-        *reinterpret_cast<uint4*>(Xs + r * XP + q * 8) = *reinterpret_cast<const uint4*>(a.w.Xq + (b0 + r) * D + q * 8);
+    // ---- prologue: the positive pairs, in fp32
+    const int p = tid >> 4, lp = tid & 15;           // pair of the tile, lane of the pair
+    const int64_t b = b0 + p;
+    const bool live = b < a.B;
+    float4 dxp[NCH];                                 // lr g0 c
+    float loss = 0.0f;
+    {
+        float4 x[NCH], c[NCH];
+        float s0 = 0.0f;
+        if (live) {
+            const int2 pr = a.pairs[b];
+            const float4* xrow = a.X + static_cast<int64_t>(pr.x) * (D / 4);
+            const float4* crow = a.C + static_cast<int64_t>(pr.y) * (D / 4);
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) { x[i] = xrow[lp + 16 * i]; c[i] = crow[lp + 16 * i]; }
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) s0 += dot4(x[i], c[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) { x[i] = make_float4(0.f, 0.f, 0.f, 0.f); c[i] = x[i]; }
+        }
+        s0 = group_sum<16>(s0);
+        const float g0 = live ? a.lr * (1.0f - sigmoidf(s0)) : 0.0f;
+        if (LOSS && live && lp == 0) loss = softplusf(-s0);
+        float4* dcs = reinterpret_cast<float4*>(a.w.dcs + b * D);
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const int ci = lp + 16 * i;
+            dxp[i] = make_float4(g0 * c[i].x, g0 * c[i].y, g0 * c[i].z, g0 * c[i].w);
+            if (live) dcs[ci] = make_float4(g0 * x[i].x, g0 * x[i].y, g0 * x[i].z, g0 * x[i].w);
+            *reinterpret_cast<uint2*>(Xs + p * XP + 4 * ci) = make_uint2(pack2(x[i].x, x[i].y), pack2(x[i].z, x[i].w));   // padding rows: zero
+        }
     }
     __syncthreads();
-    // by-product: the transposed copy the dC product reads
-    for (int col = tid; col < D && blockIdx.y == 0; col += kScoreThreads) {
-        uint16_t* out = a.w.XqT + static_cast<int64_t>(col) * Bp + b0;
+    // by-product: the transposed copy the dC product reads, 64 contiguous bytes per column
+    if (tid < D) {
+        uint4* out = reinterpret_cast<uint4*>(a.w.XqT + static_cast<int64_t>(tid) * Bp + b0);
 #pragma unroll
-        for (int r0 = 0; r0 < kRowTile; r0 += 8) {
-            uint32_t p[4];
+        for (int q = 0; q < 4; ++q) {
+            uint32_t v[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                p[i] = Xs[(r0 + 2 * i) * XP + col] | (static_cast<uint32_t>(Xs[(r0 + 2 * i + 1) * XP + col]) << 16);
-            *reinterpret_cast<uint4*>(out + r0) = make_uint4(p[0], p[1], p[2], p[3]);
+                v[i] = Xs[(8 * q + 2 * i) * XP + tid] | (static_cast<uint32_t>(Xs[(8 * q + 2 * i + 1) * XP + tid]) << 16);
+            out[q] = make_uint4(v[0], v[1], v[2], v[3]);
         }
     }
+    f32x16 acc_dx;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc_dx[i] = 0.0f;
+    const uint4* SP = reinterpret_cast<const uint4*>(a.w.CqP);     // one uint4 per lane and fragment
+    const uint4* TP = reinterpret_cast<const uint4*>(a.w.CqTP);
+    const int steps_all = a.N / 16;                                // contraction steps of dX over all negatives
+    // A fragments of S: row l % 32, contraction indices 16 s + 8 (l / 32) ..; A fragments of dX: the same of G
+    const uint16_t* xa = Xs + (l & 31) * XP + 8 * (l >> 5);
+    const uint16_t* ga = Gs + (l & 31) * GP + 8 * (l >> 5);
 
-    f32x16 acc_dx[DT];
+    // The operand fragments come straight from memory (L2: every workgroup streams the same 2 N d bytes), 1 KB per
+    // wavefront and step, and each wavefront has only one other on its SIMD to hide their latency: so they are
+    // requested as early as their registers are free: those of a pass's dX product and those of the next pass's S
+    // product as soon as the S product has consumed its own.
+    uint4 bS[KS];
+    if (w * 32 < a.N) {
+        const uint4* src = SP + static_cast<size_t>(w) * KS * 64 + l;
 #pragma unroll
-    for (int t = 0; t < DT; ++t)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc_dx[t][i] = 0.0f;
-    float loss = 0.0f;
-
-    // this workgroup's share of the negatives, in chunks of 64; the next chunk's rows travel from
-    // memory into registers while the current one is being used
-    constexpr int CPT = kNegChunk * (D / 8) / kScoreThreads;   // 16-byte pieces of Cs per thread (= of CTs)
-    const int n_share = a.N / static_cast<int>(gridDim.y);
-    const int n_begin = blockIdx.y * n_share, n_end = n_begin + n_share;
-    u32x4 pc[CPT], pt[CPT];
-    // piece c of the chunk: Cs row c / (D/8), 16-byte column c % (D/8); CTs row c / 8, column c % 8
-    const uint16_t* src_c[CPT];
-    const uint16_t* src_t[CPT];
-#pragma unroll
-    for (int i = 0; i < CPT; ++i) {
-        const int c = tid + i * kScoreThreads;
-        src_c[i] = a.w.Cq + static_cast<int64_t>(n_begin + c / (D / 8)) * D + (c % (D / 8)) * 8;
-        src_t[i] = a.w.CqT + static_cast<int64_t>(c / (kNegChunk / 8)) * a.N + n_begin + (c % (kNegChunk / 8)) * 8;
-        pc[i] = *reinterpret_cast<const u32x4*>(src_c[i]);
-        pt[i] = *reinterpret_cast<const u32x4*>(src_t[i]);
+        for (int s = 0; s < KS; ++s) bS[s] = src[s * 64];
     }
-    for (int n0 = n_begin; n0 < n_end; n0 += kNegChunk) {
+    for (int n0 = 0; n0 < a.N; n0 += kNegChunk) {
+        const int nblock = (n0 >> 5) + w;                 // this wavefront's block of 32 negatives (whole blocks: N % 128 == 0)
+        const bool s_active = nblock * 32 < a.N;
+        const bool x_active = w < CB;                     // this wavefront has a block of 32 columns of dX
+        const int steps = min(kNegChunk / 16, steps_all - (n0 >> 4));   // 16, or 8 in a last pass of 128 negatives
+        const uint4* tsrc = TP + (static_cast<size_t>(w) * steps_all + (n0 >> 4)) * 64 + l;
+        uint4 bT0[8], bT1[8];
+        f32x16 sacc;
+        if (s_active) {
 #pragma unroll
-        for (int i = 0; i < CPT; ++i) {
-            const int c = tid + i * kScoreThreads;
-            *reinterpret_cast<u32x4*>(Cs + (c / (D / 8)) * XP + (c % (D / 8)) * 8) = pc[i];
-            *reinterpret_cast<u32x4*>(CTs + (c / (kNegChunk / 8)) * TP + (c % (kNegChunk / 8)) * 8) = pt[i];
+            for (int i = 0; i < 16; ++i) sacc[i] = 0.0f;
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*reinterpret_cast<const uint4*>(xa + 16 * s)), as_bf16x8(bS[s]), sacc, 0, 0, 0);
         }
-        __syncthreads();
-        if (n0 + kNegChunk < n_end) {
+        if (x_active) {                                   // (after the S product: waits on loads are in issue order)
 #pragma unroll
-            for (int i = 0; i < CPT; ++i) {
-                src_c[i] += kNegChunk * D;
-                src_t[i] += kNegChunk;
-                pc[i] = *reinterpret_cast<const u32x4*>(src_c[i]);
-                pt[i] = *reinterpret_cast<const u32x4*>(src_t[i]);
+            for (int s = 0; s < 8; ++s) bT0[s] = tsrc[s * 64];
+            if (steps > 8) {
+#pragma unroll
+                for (int s = 0; s < 8; ++s) bT1[s] = tsrc[(8 + s) * 64];
             }
         }
-
-        // S = Xq . Cq^T for 32 pairs x 32 negatives
-        f32x16 s;
+        if (n0 + kNegChunk + w * 32 < a.N) {              // the S operands of the next pass
+            const uint4* src = SP + static_cast<size_t>(nblock + kNegChunk / 32) * KS * 64 + l;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s[i] = 0.0f;
-        const uint16_t* xa = Xs + (rh * 32 + (l & 31)) * XP + (l >> 5) * 8;
-        const uint16_t* cb = Cs + (ch * 32 + (l & 31)) * XP + (l >> 5) * 8;
-#pragma unroll
-        for (int k0 = 0; k0 < D; k0 += 16) {
-            const bf16x8 av = as_bf16x8(*reinterpret_cast<const uint4*>(xa + k0));
-            const bf16x8 bv = as_bf16x8(*reinterpret_cast<const uint4*>(cb + k0));
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, s, 0, 0, 0);
+            for (int s = 0; s < KS; ++s) bS[s] = src[s * 64];
         }
-        // G = -neg_scale * sigmoid(S), zero for padding rows; into LDS as bf16
+        if (s_active) {
+            // G = -neg_scale * sigmoid(S), zero for padding rows; into LDS as bf16
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int row = rh * 32 + (i >> 2) * 8 + (l >> 5) * 4 + (i & 3);
-            const int col = ch * 32 + (l & 31);
-            const bool valid = b0 + row < a.B;
-            const float g = valid ? -a.neg_scale * fast_sigmoidf(s[i]) : 0.0f;
-            if (a.loss && valid) loss += a.neg_scale * softplusf(s[i]);
-            Gs[row * TP + g_col(row, col)] = to_bf16(g);
+            for (int i = 0; i < 16; ++i) {
+                const int row = (i >> 2) * 8 + (l >> 5) * 4 + (i & 3);
+                const bool valid = b0 + row < a.B;
+                const float g = valid ? -a.neg_scale * fast_sigmoidf(sacc[i]) : 0.0f;
+                if (LOSS && valid) loss += a.neg_scale * softplusf(sacc[i]);
+                Gs[row * GP + w * 32 + (l & 31)] = to_bf16(g);
+            }
         }
-        __syncthreads();
-
-        // G^T to memory: 64 negatives x 128 pairs, 256 contiguous bytes per negative
+        lds_barrier();
+        // G^T to memory: one negative of the pass per two threads, 16 pairs (32 bytes) each
         {
-            const int neg = tid >> 3, part = tid & 7;
-            uint32_t p[8];
+            const int neg = tid >> 1, half = tid & 1;
+            if (n0 + neg < a.N) {
+                uint32_t v[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
-                p[i] = Gs[(part * 16 + 2 * i) * TP + g_col(part * 16, neg)] |
-                       (static_cast<uint32_t>(Gs[(part * 16 + 2 * i + 1) * TP + g_col(part * 16, neg)]) << 16);
-            uint4* out = reinterpret_cast<uint4*>(a.w.GT + static_cast<int64_t>(n0 + neg) * Bp + b0 + part * 16);
-            out[0] = make_uint4(p[0], p[1], p[2], p[3]);
-            out[1] = make_uint4(p[4], p[5], p[6], p[7]);
-        }
-        // dX += G . Cq for 32 pairs x D/2 columns over the 64 negatives of the chunk
-        const uint16_t* ga = Gs + (rh * 32 + (l & 31)) * TP;
-#pragma unroll
-        for (int kk = 0; kk < kNegChunk; kk += 16) {
-            const bf16x8 av = as_bf16x8(*reinterpret_cast<const uint4*>(ga + g_col(rh * 32 + (l & 31), kk + (l >> 5) * 8)));
-#pragma unroll
-            for (int t = 0; t < DT; ++t) {
-                const uint16_t* tb = CTs + (ch * (D / 2) + t * 32 + (l & 31)) * TP + (l >> 5) * 8 + kk;
-                acc_dx[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, as_bf16x8(*reinterpret_cast<const uint4*>(tb)),
-                                                                    acc_dx[t], 0, 0, 0);
+                for (int i = 0; i < 8; ++i)
+                    v[i] = Gs[(half * 16 + 2 * i) * GP + neg] | (static_cast<uint32_t>(Gs[(half * 16 + 2 * i + 1) * GP + neg]) << 16);
+                uint4* out = reinterpret_cast<uint4*>(a.w.GT + static_cast<int64_t>(n0 + neg) * Bp + b0 + half * 16);
+                out[0] = make_uint4(v[0], v[1], v[2], v[3]);
+                out[1] = make_uint4(v[4], v[5], v[6], v[7]);
             }
         }
-        __syncthreads();   // Cs, CTs, Gs are rewritten by the next chunk
+        // dX += G . Cq for this wavefront's block of 32 columns over the negatives of the pass
+        if (x_active) {
+#pragma unroll
+            for (int s = 0; s < 8; ++s)
+                acc_dx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*reinterpret_cast<const uint4*>(ga + 16 * s)), as_bf16x8(bT0[s]), acc_dx, 0, 0, 0);
+            if (steps > 8) {
+#pragma unroll
+                for (int s = 0; s < 8; ++s)
+                    acc_dx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*reinterpret_cast<const uint4*>(ga + 16 * (8 + s))), as_bf16x8(bT1[s]), acc_dx, 0, 0, 0);
+            }
+        }
+        lds_barrier();   // G is rewritten by the next pass (and the rows' LDS by the epilogue)
     }
 
-    float* dxn = a.w.dXn + static_cast<int64_t>(blockIdx.y) * Bp * D;
-#pragma unroll
-    for (int t = 0; t < DT; ++t)
+    // ---- epilogue: dX to the pairs' lanes
+    if (w < CB) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const int row = rh * 32 + (i >> 2) * 8 + (l >> 5) * 4 + (i & 3);
-            const int col = ch * (D / 2) + t * 32 + (l & 31);
-            dxn[(b0 + row) * D + col] = acc_dx[t][i];
+            const int row = (i >> 2) * 8 + (l >> 5) * 4 + (i & 3);
+            dXs[row * DP + w * 32 + (l & 31)] = acc_dx[i];
         }
-    if (a.loss) {
+    }
+    lds_barrier();
+    if (live) {
+        float4* dxs = reinterpret_cast<float4*>(a.w.dxs + b * D);
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const int ci = lp + 16 * i;
+            const float4 n = *reinterpret_cast<const float4*>(dXs + p * DP + 4 * ci);
+            dxs[ci] = make_float4(fmaf(a.lr, n.x, dxp[i].x), fmaf(a.lr, n.y, dxp[i].y), fmaf(a.lr, n.z, dxp[i].z), fmaf(a.lr, n.w, dxp[i].w));
+        }
+    }
+    if (LOSS) {
         __shared__ double sh[kScoreThreads / 64];
         for (int off = 32; off > 0; off >>= 1) loss += __shfl_xor(loss, off, 64);
         if (l == 0) sh[w] = static_cast<double>(loss);
@@ -404,7 +417,7 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(ScoresArgs a)
         if (tid == 0) {
             double total = 0.0;
             for (int i = 0; i < kScoreThreads / 64; ++i) total += sh[i];
-            atomicAdd(a.loss, total);
+            if (total != 0.0) atomicAdd(a.loss, total);
         }
     }
 }
@@ -521,7 +534,6 @@ struct UpdateArgs {
     int64_t B;
     int32_t N;
     float lr;
-    int32_t neg_split;   // partial sums of dXn that were written
     SharedWs w;
 };
 
@@ -546,10 +558,8 @@ __global__ __launch_bounds__(256) void update_shared_kernel(UpdateArgs a)
         const bool c_sole = sole_reference(a.w, static_cast<uint32_t>(pr.y) | kContextKey, static_cast<uint32_t>(2 * gidx + 1));
         float* xrow = a.X + static_cast<int64_t>(pr.x) * D;
         float* crow = a.C + static_cast<int64_t>(pr.y) * D;
-        const float* dxp = a.w.dxp + gidx * D;
-        const float* dxn = a.w.dXn + gidx * D;
-        const int64_t part = a.w.Bp * D;
-        const float* uctx = a.w.uctx + gidx * D;
+        const float* dxs = a.w.dxs + gidx * D;
+        const float* dcs = a.w.dcs + gidx * D;
         // all loads of a group are issued before its first store or atomic
         float4 x4[2], c4[2];
         float x1[8], c1[8];
@@ -557,35 +567,21 @@ __global__ __launch_bounds__(256) void update_shared_kernel(UpdateArgs a)
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 const int ci = lg + i * G;
-                float4 n = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-                for (int s = 0; s < kNegSplit; ++s)
-                    if (s < a.neg_split) n = add4(n, reinterpret_cast<const float4*>(dxn + s * part)[ci]);
-                const float4 p = reinterpret_cast<const float4*>(dxp)[ci];
-                const float4 r = reinterpret_cast<const float4*>(xrow)[ci];
-                x4[i] = make_float4(r.x + fmaf(a.lr, n.x, p.x), r.y + fmaf(a.lr, n.y, p.y), r.z + fmaf(a.lr, n.z, p.z),
-                                    r.w + fmaf(a.lr, n.w, p.w));
+                x4[i] = add4(reinterpret_cast<const float4*>(xrow)[ci], reinterpret_cast<const float4*>(dxs)[ci]);
             }
         } else {
 #pragma unroll
-            for (int m = 0; m < 8; ++m) {
-                const int e = lg + m * G;
-                float n = 0.0f;
-#pragma unroll
-                for (int s = 0; s < kNegSplit; ++s)
-                    if (s < a.neg_split) n += dxn[s * part + e];
-                x1[m] = fmaf(a.lr, n, dxp[e]);
-            }
+            for (int m = 0; m < 8; ++m) x1[m] = dxs[lg + m * G];
         }
         if (c_sole) {
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 const int ci = lg + i * G;
-                c4[i] = add4(reinterpret_cast<const float4*>(crow)[ci], reinterpret_cast<const float4*>(uctx)[ci]);
+                c4[i] = add4(reinterpret_cast<const float4*>(crow)[ci], reinterpret_cast<const float4*>(dcs)[ci]);
             }
         } else {
 #pragma unroll
-            for (int m = 0; m < 8; ++m) c1[m] = uctx[lg + m * G];
+            for (int m = 0; m < 8; ++m) c1[m] = dcs[lg + m * G];
         }
         if (x_sole) {
 #pragma unroll
@@ -643,39 +639,28 @@ hipError_t run_shared(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev
 {
     constexpr int G = D / 8;
     constexpr int GROUPS = 256 / G;
-    StageArgs sa{};
-    sa.X = reinterpret_cast<const float4*>(t->vertex); sa.C = reinterpret_cast<const float4*>(t->context);
-    sa.pairs = reinterpret_cast<const int2*>(pairs_dev); sa.B = B; sa.Bp = w.Bp; sa.N = N; sa.lr = lr;
-    sa.batch_index = batch_index; sa.k0 = static_cast<uint32_t>(t->seed); sa.k1 = static_cast<uint32_t>(t->seed >> 32);
-    sa.alias = al->table; sa.alias_n = static_cast<uint64_t>(al->n); sa.alias_base = al->base;
-    sa.w = w; sa.neg_out = neg_out; sa.loss = loss;
-    hipLaunchKernelGGL(stage_kernel<D>, dim3(static_cast<unsigned>((w.Bp + N + GROUPS - 1) / GROUPS)), dim3(256), 0, st, sa);
+    PrepNegArgs pa{};
+    pa.C = reinterpret_cast<const float4*>(t->context); pa.pairs = reinterpret_cast<const int2*>(pairs_dev);
+    pa.B = B; pa.N = N; pa.batch_index = batch_index;
+    pa.k0 = static_cast<uint32_t>(t->seed); pa.k1 = static_cast<uint32_t>(t->seed >> 32);
+    pa.alias = al->table; pa.alias_n = static_cast<uint64_t>(al->n); pa.alias_base = al->base;
+    pa.w = w; pa.neg_out = neg_out;
+    // threads: a lane group per negative, one per pair reference, one per 16 flags
+    int64_t threads = static_cast<int64_t>(N) * G;
+    if (threads < 2 * B) threads = 2 * B;
+    if (threads < (static_cast<int64_t>(w.hash_mask) + 16) / 16) threads = (static_cast<int64_t>(w.hash_mask) + 16) / 16;
+    hipLaunchKernelGGL(prep_kernel<D>, dim3(static_cast<unsigned>((threads + 255) / 256)), dim3(256), 0, st, pa);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
-    // shares of the negatives must be whole 64-negative chunks
-    const unsigned neg_split = (N % (kNegSplit * kNegChunk) == 0) ? kNegSplit : 2;
     ScoresArgs ca{};
-    ca.w = w; ca.B = B; ca.N = N; ca.neg_scale = neg_scale; ca.loss = loss; ca.pairs = sa.pairs;
-    const size_t lds_bytes = (static_cast<size_t>(kRowTile + kNegChunk) * (D + 8) + static_cast<size_t>(D + kRowTile) * (kNegChunk + 8)) * 2;
-    // more than the default 64 KB of dynamic LDS (gfx950 has 160 KB per CU): asked for once per device
-    // and kernel, so that later calls are kernel launches only (a caller may be capturing the stream)
-    {
-        static std::atomic<uint64_t> lds_raised{0};
-        int device = 0;
-        e = hipGetDevice(&device);
-        if (e != hipSuccess) return e;
-        const uint64_t bit = 1ull << (device & 63);
-        if (!(lds_raised.load(std::memory_order_acquire) & bit)) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(scores_kernel<D>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    static_cast<int>((static_cast<size_t>(kRowTile + kNegChunk) * (D + 8) +
-                                                      static_cast<size_t>(D + kRowTile) * (kNegChunk + 8)) * 2));
-            if (e != hipSuccess) return e;
-            lds_raised.fetch_or(bit, std::memory_order_release);
-        }
-    }
+    ca.X = reinterpret_cast<const float4*>(t->vertex); ca.C = pa.C;
+    ca.w = w; ca.B = B; ca.N = N; ca.lr = lr; ca.neg_scale = neg_scale; ca.loss = loss; ca.pairs = pa.pairs;
     const bool timed = profile_begin(t, st);
-    hipLaunchKernelGGL(scores_kernel<D>, dim3(static_cast<unsigned>(w.Bp / kRowTile), neg_split), dim3(kScoreThreads), lds_bytes, st, ca);
+    if (loss)
+        hipLaunchKernelGGL((scores_kernel<D, true>), dim3(static_cast<unsigned>(w.Bp / kPairTile)), dim3(kScoreThreads), 0, st, ca);
+    else
+        hipLaunchKernelGGL((scores_kernel<D, false>), dim3(static_cast<unsigned>(w.Bp / kPairTile)), dim3(kScoreThreads), 0, st, ca);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (timed) profile_end(t, st);
@@ -691,7 +676,7 @@ hipError_t run_shared(ne_tables* t, const ne_alias* al, const int32_t* pairs_dev
     if (e != hipSuccess) return e;
 
     UpdateArgs ua{};
-    ua.X = t->vertex; ua.C = t->context; ua.pairs = sa.pairs; ua.B = B; ua.N = N; ua.lr = lr; ua.neg_split = static_cast<int32_t>(neg_split); ua.w = w;
+    ua.X = t->vertex; ua.C = t->context; ua.pairs = pa.pairs; ua.B = B; ua.N = N; ua.lr = lr; ua.w = w;
     hipLaunchKernelGGL(update_shared_kernel<D>, dim3(static_cast<unsigned>((B + N + GROUPS - 1) / GROUPS)), dim3(256), 0, st, ua);
     return hipGetLastError();
 }
