@@ -359,6 +359,7 @@ static int run_on_threads(share_job* jobs, pthread_t* tid, int64_t T, void* (*fn
     return rc;
 }
 
+/* (Not reentrant: one call at a time per process.)                                                  */
 /* Memory of thread t's four delta maps, kept from one call to the next (fresh pages cost more than   */
 /* the arithmetic when every call maps and unmaps a few hundred MB per thread).  slot_of is all -1    */
 /* between calls: a call resets the entries it has set.                                               */
