@@ -1,4 +1,4 @@
-"""Parity at the benchmark's full sizes and launch configuration (ne_train_block, batch 65536).
+"""Parity at the benchmark's full sizes and launch configuration (ne_train_runs / ne_train_block, batch 65536).
 
 Config 2 (1 M nodes): the oracle runs the same batches on host copies of the tables; every element is
 compared.  Config 3 (100 M nodes, 102 GB of tables): host copies are impossible, so sampled table rows
@@ -149,6 +149,65 @@ def test_config3_sampled_rows():
         assert int(neg.min()) >= lo and int(neg.max()) < hi
         want = oracle.sample_negatives(seed, 1000 * k, 2048, K, thr, al, lo)
         assert np.array_equal(neg[:2048].cpu().numpy(), want)
+
+
+def test_config3_runs_in_the_benchmark_configuration():
+    """bench.py trains config 3 through ne_train_runs: the runs of consecutive batches of the (src-block, ctx-block)
+    buckets in one call, every batch's id-only work riding in the launches of the batch before it, also across a
+    change of bucket and alias table.  Here: two buckets of the orthogonal order, three batches each, in that
+    configuration; then, from the same initial tables (the seeded init is reproducible), the same batches one call
+    each, every one checked against the oracle on sampled rows; the two end states must agree on every row the
+    batches name (sampled) to 1e-5 - the arithmetic is the same, only the order of atomic adds differs - and
+    bit for bit on rows they do not name."""
+    say("config 3 through ne_train_runs: 2 buckets x 3 batches of 65536, 100M nodes")
+    V, d, K, B, seed, grid = 100_000_000, 128, 5, 65536, 2, 4
+    rng = np.random.default_rng(3)
+    degree = wl.rmat_degrees(V, 400_000_000, seed, device=DEV)
+    pairs = wl.rmat_pairs(V, 100 * B, seed, device=DEV)
+    bp = wl.bucket_pairs(pairs, V, grid)
+    sched = [s for s in wl.orthogonal_schedule(bp, B) if s[1] == B]
+    buckets = []
+    for s in sched:                                   # the first two buckets of the schedule with three whole batches
+        key = (s[2], s[3])
+        if key not in [b[0] for b in buckets]:
+            same = [x for x in sched if (x[2], x[3]) == key][:3]
+            if len(same) == 3 and same[2][0] == same[0][0] + 2 * B:
+                buckets.append((key, same))
+        if len(buckets) == 2:
+            break
+    assert len(buckets) == 2 and buckets[0][0][0] != buckets[1][0][0] and buckets[0][0][1] != buckets[1][0][1]
+    aliases, oracles = {}, {}
+    for (bi, bj), _ in buckets:
+        lo, hi = bj * bp.block_rows, min((bj + 1) * bp.block_rows, V)
+        deg_blk = degree[lo:hi].clamp(max=2**32 - 1).cpu().numpy().astype(np.uint32)
+        at = torch.empty((hi - lo, 2), dtype=torch.int32, device=DEV)
+        aliases[bj] = (ne.ne_build_neg_alias(deg_blk, lo, at), at)
+    t = make_tables(V, d, K, B, seed)
+    lrs = [0.025, 0.024, 0.023, 0.022, 0.021, 0.020]
+    runs, base = [], 0
+    for (bi, bj), same in buckets:
+        runs.append((aliases[bj][0], bp.pairs[same[0][0]:same[0][0] + 3 * B], base))
+        base += 3 * B
+    ne.ne_train_runs(t, runs, B, K, lrs)
+    torch.cuda.synchronize()
+    # rows to compare: a sample of the rows the six batches name, and rows they do not name
+    named_x = torch.unique(torch.cat([r[1][:, 0] for r in runs]).long())
+    named_c = torch.unique(torch.cat([r[1][:, 1] for r in runs]).long())
+    sx = named_x[torch.from_numpy(rng.choice(named_x.numel(), 20000, replace=False)).to(DEV)]
+    sc = named_c[torch.from_numpy(rng.choice(named_c.numel(), 20000, replace=False)).to(DEV)]
+    fused_x, fused_c = t.vertex[sx].clone(), t.context[sc].clone()
+    # the same batches, one call each, from the same initial tables, each against the oracle
+    t2 = ne.ne_create_tables(t.vertex, t.context, seed, init=True, max_batch=B, max_negatives=K, workspace=t.workspace)
+    k = 0
+    for (bi, bj), same in buckets:
+        for (s, n, _, _) in same:
+            sampled_row_check(t2, aliases[bj][0], bp.pairs[s:s + n], K, lrs[k], k * B, 128, rng)
+            k += 1
+    ex = rowwise_rel_err(fused_x.cpu().numpy(), t.vertex[sx].cpu().numpy())
+    ec = rowwise_rel_err(fused_c.cpu().numpy(), t.context[sc].cpu().numpy())
+    say(f"  one ne_train_runs call against one call per batch: row error X {ex:.2e} C {ec:.2e} on {sx.numel()} + {sc.numel()} named rows")
+    assert ex <= 1e-5 and ec <= 1e-5
+    assert not torch.equal(fused_x, torch.zeros_like(fused_x))
 
 
 def test_maximum_batch_size():
