@@ -110,7 +110,8 @@ struct PrepArgs {
     int32_t alias_base;
     unsigned long long* slots;
     uint32_t mask;        // cap - 1
-    uint8_t* shared;
+    uint8_t* shared;      // per hash position: the row there is named more than once (what the apply sweep reads)
+    uint8_t* refshared;   // per reference: the same fact, where the train kernel reads it without a dependent lookup
     int32_t* ids;
     uint32_t* posbuf;
     int32_t* neg_out;
@@ -162,6 +163,7 @@ __device__ __forceinline__ void claim_pair_refs(const PrepArgs& a, unsigned bloc
                 if (a.neg_out) a.neg_out[static_cast<int64_t>(b[u]) * a.K + (j[u] - 2)] = id[u];
             }
             a.ids[t[u]] = id[u];
+            a.refshared[t[u]] = 0;   // resolve sets it, one launch later
             const uint32_t key = static_cast<uint32_t>(id[u]) | (j[u] == 0 ? 0u : 0x80000000u);
             a.slots[hash_key(key, a.mask)] = (static_cast<unsigned long long>(key) << 32) | t[u];
         }
@@ -231,6 +233,7 @@ __device__ __forceinline__ void claim_walk_refs(const PrepArgs& a, unsigned bloc
         }
         if (!valid[u]) id[u] = -1;
         a.ids[t[u]] = id[u];
+        a.refshared[t[u]] = 0;
         if (valid[u]) {
             const uint32_t key = static_cast<uint32_t>(id[u]) | (kk[u] == -2 ? 0u : 0x80000000u);
             a.slots[hash_key(key, a.mask)] = (static_cast<unsigned long long>(key) << 32) | t[u];
@@ -316,6 +319,7 @@ __device__ __forceinline__ void claim_seg_refs(const PrepArgs& a, unsigned block
         }
         if (!valid[u]) id[u] = -1;
         a.ids[t[u]] = id[u];
+        a.refshared[t[u]] = 0;
         if (valid[u]) {
             const uint32_t key = static_cast<uint32_t>(id[u]) | (kk[u] == -2 ? 0u : 0x80000000u);
             a.slots[hash_key(key, a.mask)] = (static_cast<unsigned long long>(key) << 32) | t[u];
@@ -359,7 +363,11 @@ __device__ __forceinline__ void resolve_refs(const PrepArgs& a, unsigned block)
         if (static_cast<uint32_t>(owner[u] >> 32) == key[u]) {
             // my row owns its home position; any reference but the one whose store landed last
             // proves that the row is named at least twice
-            if (static_cast<uint32_t>(owner[u]) != t[u]) a.shared[p] = 1;
+            if (static_cast<uint32_t>(owner[u]) != t[u]) {
+                a.shared[p] = 1;
+                a.refshared[t[u]] = 1;
+                a.refshared[static_cast<uint32_t>(owner[u])] = 1;   // the owner cannot tell by itself
+            }
         } else {
             // another row owns the home position: probe onwards.  Positions only ever go from empty
             // to occupied here, and the table holds at most half as many keys as positions, so the walk ends.
@@ -368,7 +376,12 @@ __device__ __forceinline__ void resolve_refs(const PrepArgs& a, unsigned block)
                 p = (p + 1) & a.mask;
                 const unsigned long long prev = atomicCAS(&a.slots[p], kEmptySlot, mine);
                 if (prev == kEmptySlot) break;
-                if (static_cast<uint32_t>(prev >> 32) == key[u]) { a.shared[p] = 1; break; }
+                if (static_cast<uint32_t>(prev >> 32) == key[u]) {
+                    a.shared[p] = 1;
+                    a.refshared[t[u]] = 1;
+                    a.refshared[static_cast<uint32_t>(prev)] = 1;
+                    break;
+                }
             }
         }
         a.posbuf[t[u]] = p;
@@ -439,7 +452,7 @@ struct TrainArgs {
     float lr;
     const int32_t* ids;
     const uint32_t* posbuf;
-    const uint8_t* shared;
+    const uint8_t* refshared;   // per reference: its row is named by another reference too
     float* delta;
     // shared rows, list path: the first list_cap references to arrive at a row (0 = path off)
     uint32_t list_cap;
@@ -625,7 +638,7 @@ __global__ __launch_bounds__(kTrainThreads) void train_kernel(TrainArgs a, PrepA
     if (lg < R) {
         id_mine = a.ids[ref_mine];
         pos_mine = a.posbuf[ref_mine];
-        shared_mine = a.shared[pos_mine];
+        shared_mine = a.refshared[ref_mine];
     }
     const int shared0 = __shfl(shared_mine, 0, G);
     const uint32_t pos0 = __shfl(pos_mine, 0, G);
@@ -695,7 +708,7 @@ __global__ __launch_bounds__(kTrainThreads) void train_walk_kernel(TrainArgs a, 
     const int32_t src = a.ids[ref0];
     if (src < 0) return;    // no pair starts at this position (uniform over the group)
     const uint32_t pos0 = a.posbuf[ref0];
-    const int shared0 = a.shared[pos0];
+    const int shared0 = a.refshared[ref0];
     const uint32_t rank0 = shared0 ? arrival_rank<G>(a, pos0, lg) : ~0u;
 
     float4* xrow = a.X + static_cast<int64_t>(src) * d4;
@@ -722,7 +735,7 @@ __global__ __launch_bounds__(kTrainThreads) void train_walk_kernel(TrainArgs a, 
             id_mine = a.ids[ref];
             if (id_mine >= 0) {
                 pos_mine = a.posbuf[ref];
-                shared_mine = a.shared[pos_mine];
+                shared_mine = a.refshared[ref];
             }
         }
         if (__shfl(id_mine, 0, G) < 0) continue;   // the walk has no pair j here; a pair's references exist together
@@ -799,7 +812,7 @@ __global__ __launch_bounds__(kTrainThreads) void train_seg_kernel(TrainArgs a, P
     float4* xrow = a.X;
     if (src >= 0) {
         pos_x = a.posbuf[ref0 + grp];
-        shared_x = a.shared[pos_x];
+        shared_x = a.refshared[ref0 + grp];
         if (shared_x) rank_x = arrival_rank<G>(a, pos_x, lg);
         xrow = a.X + static_cast<int64_t>(src) * d4;
 #pragma unroll
@@ -854,7 +867,7 @@ __global__ __launch_bounds__(kTrainThreads) void train_seg_kernel(TrainArgs a, P
                 if (lg < K) {
                     id_mine = a.ids[ref];
                     pos_mine = a.posbuf[ref];
-                    shared_mine = a.shared[pos_mine];
+                    shared_mine = a.refshared[ref];
                 }
                 context_rows_of_pair<G, NCH, JB, 0, false>(a, K - 1, d4, d, xr, xt, dx, id_mine, pos_mine, shared_mine,
                                                            static_cast<uint32_t>(ref), lg);
@@ -879,7 +892,7 @@ __global__ __launch_bounds__(kTrainThreads) void train_seg_kernel(TrainArgs a, P
         if (id < 0) continue;
         const int64_t ref = ref0 + E + row;
         const uint32_t pos_c = a.posbuf[ref];
-        const int shared_c = a.shared[pos_c];
+        const int shared_c = a.refshared[ref];
         const uint32_t rank_c = shared_c ? arrival_rank<G>(a, pos_c, lg) : ~0u;
         float4 cr[NCH], dc[NCH];
 #pragma unroll
@@ -1299,6 +1312,7 @@ bool workspace_layout(int32_t dim, int64_t max_B, int32_t max_K, char* base, Wor
         w->prep[i].shared = reinterpret_cast<uint8_t*>(take(cap));
         w->prep[i].ids = reinterpret_cast<int32_t*>(take(refs * 4));
         w->prep[i].posbuf = reinterpret_cast<uint32_t*>(take(refs * 4));
+        w->prep[i].refshared = reinterpret_cast<uint8_t*>(take(refs));
     }
     w->delta = reinterpret_cast<float*>(take(cap * static_cast<size_t>(dim) * 4));
     w->count = reinterpret_cast<uint32_t*>(take(cap * 4));
@@ -1379,7 +1393,7 @@ ne_status run_batches(ne_tables* t, int64_t n_batches, int64_t R, int32_t window
         TrainArgs ta{};
         ta.X = reinterpret_cast<float4*>(t->vertex); ta.C = reinterpret_cast<float4*>(t->context);
         ta.B = cur.refs / R; ta.window = window; ta.K = K; ta.d4 = t->dim / 4; ta.lr = lr_host[i];
-        ta.ids = ps.ids; ta.posbuf = ps.posbuf; ta.shared = ps.shared; ta.delta = w.delta;
+        ta.ids = ps.ids; ta.posbuf = ps.posbuf; ta.refshared = ps.refshared; ta.delta = w.delta;
         BatchTuning tune = batch_tuning(t, cur.refs);
         if (direct) tune.list_cap = 0;   // no slots, no lists: shared rows take their atomics on the table itself
         ta.direct = direct ? 1 : 0;
@@ -1670,7 +1684,7 @@ static ne_status train_runs_impl(ne_tables* t, const ne_run* runs, int64_t n_run
         pa.alias = al ? al->table : nullptr; pa.alias_n = al ? static_cast<uint64_t>(al->n) : 1; pa.alias_base = al ? al->base : 0;
         uint32_t positions = kSweepPerBlock;     // hash positions this batch uses
         while (positions < kHashFactor * static_cast<uint32_t>(bt.count * R)) positions <<= 1;
-        pa.slots = ps.slots; pa.mask = positions - 1; pa.shared = ps.shared; pa.ids = ps.ids; pa.posbuf = ps.posbuf;
+        pa.slots = ps.slots; pa.mask = positions - 1; pa.shared = ps.shared; pa.refshared = ps.refshared; pa.ids = ps.ids; pa.posbuf = ps.posbuf;
         pa.neg_out = run.neg_out_dev ? run.neg_out_dev + bt.first * K : nullptr;
         return pa;
     };
@@ -1781,7 +1795,7 @@ ne_status ne_train_walks(ne_tables* t, const ne_alias* al, const int32_t* walks_
         pa.alias = al ? al->table : nullptr; pa.alias_n = al ? static_cast<uint64_t>(al->n) : 1; pa.alias_base = al ? al->base : 0;
         uint32_t positions = kSweepPerBlock;     // hash positions this batch uses
         while (positions < kHashFactor * pa.refs) positions <<= 1;
-        pa.slots = ps.slots; pa.mask = positions - 1; pa.shared = ps.shared; pa.ids = ps.ids; pa.posbuf = ps.posbuf;
+        pa.slots = ps.slots; pa.mask = positions - 1; pa.shared = ps.shared; pa.refshared = ps.refshared; pa.ids = ps.ids; pa.posbuf = ps.posbuf;
         pa.neg_out = neg_out_dev ? neg_out_dev + first * per_walk * K : nullptr;
         return pa;
     };

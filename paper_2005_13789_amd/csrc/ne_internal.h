@@ -35,6 +35,7 @@ struct PrepSlot {
     uint8_t* shared;            // [cap]  1 <=> the row whose key sits at this position is shared
     int32_t* ids;               // [max_B][max_K+2]  src, ctx, negatives
     uint32_t* posbuf;           // [max_B][max_K+2]  final hash position of each reference
+    uint8_t* refshared;         // [max_B][max_K+2]  1 <=> another reference of the batch names this reference's row too
 };
 struct Workspace {
     PrepSlot prep[2];
